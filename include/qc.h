@@ -1,0 +1,156 @@
+/*
+ * libqc -- the quantized-linear hot path of QuantCache (arxiv 2503.06545) for one
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or framework types.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".  Buffers
+ *     are owned by the caller; the library never allocates, frees or synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work on that stream and return; they are asynchronous.
+ *   - Tensors are dense and row major: X [M, K] (token major), W [N, K] (output
+ *     channel major, the nn.Linear convention), Y [M, N];  Y = X * W^T + bias.
+ *   - Data pointers must be 16-byte aligned.
+ *   - Errors are return codes.  Argument errors are found before anything is
+ *     launched, so a failed call has no side effect.  NaN / Inf in inputs are not
+ *     detected; results are then unspecified.
+ *
+ * Quantizer (Section 3.1, Eq. (3) and Eq. (4) of the paper, in symmetric signed
+ * form; Section 4.1 "Quantization Scheme": per-channel weights, activation scales
+ * computed online).  For a row x (a token of X, or an output channel of W) and
+ * qmax = 2^(bits-1) - 1 (127 or 7):
+ *      a   = max_k |x_k|
+ *      s   = max(a, 2^-64) / qmax              IEEE binary32 division
+ *      q_k = clamp(rne(x_k / s), -qmax, qmax)  IEEE binary32 division, ties to even
+ * Scales are binary32 and are part of the bit-exact contract.
+ */
+#ifndef QC_H
+#define QC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QC_OK = 0,
+    QC_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad enum, misaligned pointer */
+    QC_ERR_UNSUPPORTED = 2, /* a size or combination this library does not implement */
+    QC_ERR_WORKSPACE = 3,   /* workspace_bytes smaller than the matching *_workspace_bytes() */
+    QC_ERR_DEVICE = 4       /* the HIP runtime refused a launch */
+} qc_status;
+
+typedef enum { QC_F32 = 0, QC_BF16 = 1 } qc_dtype;
+
+/* Activation applied after dequantization and bias (the STDiT MLP's fc1 uses GELU). */
+typedef enum { QC_EPI_NONE = 0, QC_EPI_GELU_TANH = 1, QC_EPI_GELU_ERF = 2 } qc_epilogue;
+
+/* Output element type.  QC_OUT_I32_ACC is a test hook: the raw int32 accumulators
+ * (no scales, no bias, no activation), Y then is int32 [M, N]. */
+typedef enum { QC_OUT_F32 = 0, QC_OUT_BF16 = 1, QC_OUT_I32_ACC = 2 } qc_out;
+
+/* Largest reduction length: 127 * 127 * K must stay below 2^31. */
+#define QC_MAX_K 131072
+
+const char *qc_status_string(qc_status status);
+/* Library ABI version (major * 1000 + minor). */
+int qc_version(void);
+
+/* ---- sizes (host, pure functions) ------------------------------------------------ */
+
+/* Bytes of the opaque packed-weight blob for W [N, K] at `bits` (8 or 4).
+ * 0 if the combination is unsupported (bits not 4/8, N or K < 1, K > QC_MAX_K,
+ * bits == 4 with odd K). */
+size_t qc_packed_weight_bytes(int64_t N, int64_t K, int bits);
+
+/* Bytes of scratch qc_qlinear needs: the int8 codes of X in the GEMM's tiled
+ * order plus one scale per token.  0 if M or K is out of range. */
+size_t qc_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/* Bytes of scratch qc_latent_delta needs for n elements (does not depend on n
+ * beyond a fixed cap on the number of partial sums). */
+size_t qc_latent_delta_workspace_bytes(int64_t n);
+
+/* ---- S1: offline weight quantization and packing ----------------------------------
+ * Section 4.1 "Quantization Scheme" (per-channel weight quantization) and Section
+ * 3.2 AIGQ (1) (the bit-width is fixed per layer by the importance assignment, here
+ * an argument).
+ *   W        device, float [N, K]
+ *   bits     8 or 4; bits == 4 needs an even K
+ *   packed   device, qc_packed_weight_bytes(N, K, bits) bytes, 256-byte aligned.
+ *            Opaque: a 256-byte header (layout tag, N, K, bits) then the codes in the
+ *            order the GEMM consumes them.  It can be saved and restored as bytes.
+ *   w_scale  device, float [N]: s of each output channel
+ * Errors: INVALID_ARG (null, N/K < 1, alignment), UNSUPPORTED (bits, odd K with
+ * bits 4, K > QC_MAX_K), DEVICE. */
+qc_status qc_pack_weight(const float *W, int64_t N, int64_t K, int bits, void *packed,
+                         float *w_scale, void *stream);
+
+/* Test hook: expand a packed blob back to canonical codes, int8 [N, K] row major
+ * (4-bit codes sign-extended to int8). */
+qc_status qc_unpack_weight_codes(const void *packed, int64_t N, int64_t K, int bits,
+                                 int8_t *codes, void *stream);
+
+/* ---- S2: per-token dynamic activation quantization --------------------------------
+ * Section 4.1 "Quantization Scheme" (activation parameters computed online), Eq. (3)
+ * and Eq. (4) with one scale per token row.
+ *   X        device, [M, K] of `xdt` (float or bf16), leading dimension K
+ *   qx       device, int8 [M, K] row major: the codes
+ *   x_scale  device, float [M]
+ * Errors: INVALID_ARG, UNSUPPORTED (K > QC_MAX_K), DEVICE. */
+qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
+                       float *x_scale, void *stream);
+
+/* ---- S2+S3+S4: fused quantized linear ----------------------------------------------
+ * Section 4.1 "Hardware Implementation": the DiT linear as a low-bit GEMM with the
+ * quantization and dequantization fused around it.
+ *   Y[m, n] = act( acc[m, n] * x_scale[m] * w_scale[n] + bias[n] ),
+ *   acc[m, n] = sum_k qx[m, k] * qw[n, k]   exactly, in int32
+ * where qx / x_scale are what qc_quant_act computes for X, and qw / w_scale what
+ * qc_pack_weight stored.
+ *   X          device, [M, K] of `xdt`
+ *   packed     device, blob written by qc_pack_weight(.., N, K, bits, ..)
+ *   w_scale    device, float [N]
+ *   bias       device, float [N], or NULL for no bias
+ *   Y          device, [M, N] of float (QC_OUT_F32), bf16 (QC_OUT_BF16) or int32
+ *              (QC_OUT_I32_ACC; bias and epi are then ignored)
+ *   workspace  device, >= qc_qlinear_workspace_bytes(M, K, N) bytes, 256-byte aligned;
+ *              contents on entry are irrelevant, on exit it holds the activation codes
+ *              in tiled order (see qc_debug_workspace_act)
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, DEVICE. */
+qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K, const void *packed,
+                     const float *w_scale, int bits, int64_t N, const float *bias,
+                     qc_epilogue epi, void *Y, qc_out ydt, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
+ * activation codes and scales it used out of the workspace in canonical order:
+ * qx int8 [M, K] row major, x_scale float [M]. */
+qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K, int8_t *qx,
+                                 float *x_scale, void *stream);
+
+/* ---- S5: latent change reduction ----------------------------------------------------
+ * Section 3.2 HLC, Eq. (5): the L1 norm of the change between the current latent and
+ * the cached one, with the L1 norm of the cached one to make it relative.
+ *   cur, prev  device, float [n]
+ *   out3       device, float [3]: { sum|cur-prev|, sum|prev|, ratio }.
+ *              ratio = +inf if the second sum is 0 and the first is not, 0 if both are.
+ *   workspace  device, >= qc_latent_delta_workspace_bytes(n) bytes, 256-byte aligned.
+ *              Its first 256 bytes must be zero before the first call that uses it
+ *              (qc_latent_delta_workspace_init does that); every call leaves them zero
+ *              again, so one buffer serves any number of calls on one stream.  Two
+ *              calls that overlap in time need two buffers.
+ * The result is deterministic: the same inputs give the same bits on every run.
+ * Errors: INVALID_ARG, WORKSPACE, DEVICE. */
+qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float *out3,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Zero the control words of a latent-delta workspace (a small fill kernel, safe
+ * under stream capture). */
+qc_status qc_latent_delta_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QC_H */

@@ -1,0 +1,215 @@
+"""CPU oracle for the QuantCache quantized-linear hot path -- TEST INFRASTRUCTURE ONLY.
+
+A thin numpy/ctypes front for ``qc_oracle.c`` (plain C, built with gcc).  Only the
+tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library and its Python binding never do, and this package never
+imports them.
+
+Paper passages each function follows (arxiv 2503.06545):
+  quant_act, quant_weight   Section 3.1 Eq. (3), Eq. (4) in symmetric signed form;
+                            Section 4.1 "Quantization Scheme" (per-channel weight,
+                            online activation scales); Section 3.2 AIGQ (1) for the
+                            per-layer weight bit-width
+  gemm_i32, epilogue,       Section 4.1 "Hardware Implementation" (low-bit GEMM with
+  qlinear                   fused quantize / dequantize)
+  latent_delta              Section 3.2 HLC, Eq. (5) numerator
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qc_oracle.c")
+_LIB = os.path.join(_HERE, "libqc_oracle.so")
+
+EPI_NONE, EPI_GELU_TANH, EPI_GELU_ERF = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile qc_oracle.c with gcc (-O2, no contraction, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall",
+               "-Wextra", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.orc_num_threads.restype = i32
+        lib.orc_set_num_threads.argtypes = [i32]
+        lib.orc_quant_rows_f32.argtypes = [vp, i64, i64, i32, vp, vp]
+        lib.orc_quant_rows_bf16.argtypes = [vp, i64, i64, i32, vp, vp]
+        lib.orc_pack_int4.argtypes = [vp, i64, i64, vp]
+        lib.orc_unpack_int4.argtypes = [vp, i64, i64, vp]
+        lib.orc_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.orc_gemm_i64.argtypes = [vp, vp, i64, i64, i64, vp]
+        lib.orc_epilogue_f64.argtypes = [vp, vp, vp, vp, i32, i64, i64, vp]
+        lib.orc_round_to_f32.argtypes = [vp, i64, vp]
+        lib.orc_round_to_bf16.argtypes = [vp, i64, vp]
+        lib.orc_qlinear.argtypes = [vp, i32, i64, i64, vp, vp, i64, vp, i32, vp, vp, vp, vp]
+        lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
+        for name in ("orc_set_num_threads", "orc_quant_rows_f32", "orc_quant_rows_bf16",
+                     "orc_pack_int4", "orc_unpack_int4", "orc_gemm_i32", "orc_gemm_i64",
+                     "orc_epilogue_f64", "orc_round_to_f32", "orc_round_to_bf16", "orc_qlinear",
+                     "orc_latent_delta"):
+            getattr(lib, name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_L().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _L().orc_set_num_threads(int(n))
+
+
+def qmax(bits: int) -> int:
+    """Largest code magnitude of the symmetric b-bit quantizer: 2^(b-1) - 1."""
+    return (1 << (bits - 1)) - 1
+
+
+def _quant_rows(X, qm):
+    """X: float32 [R, K] or uint16 (bf16 bit patterns) [R, K] -> (int8 codes, float32 scales)."""
+    if X.dtype == np.uint16:
+        X = _c(X, np.uint16)
+        fn = _L().orc_quant_rows_bf16
+    else:
+        X = _c(X, np.float32)
+        fn = _L().orc_quant_rows_f32
+    R, K = X.shape
+    q = np.empty((R, K), np.int8)
+    s = np.empty((R,), np.float32)
+    fn(_p(X), R, K, int(qm), _p(q), _p(s))
+    return q, s
+
+
+def quant_act(X):
+    """Per-token (per-row) symmetric int8 quantization of activations X [M, K]."""
+    return _quant_rows(X, 127)
+
+
+def quant_weight(W, bits: int):
+    """Per-output-channel symmetric quantization of W [N, K] at 8 or 4 bits."""
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
+    return _quant_rows(np.asarray(W, np.float32), qmax(bits))
+
+
+def pack_int4(codes):
+    codes = _c(codes, np.int8)
+    N, K = codes.shape
+    if K % 2:
+        raise ValueError("int4 packing needs an even K")
+    out = np.empty((N, K // 2), np.uint8)
+    _L().orc_pack_int4(_p(codes), N, K, _p(out))
+    return out
+
+
+def unpack_int4(packed, K: int):
+    packed = _c(packed, np.uint8)
+    N = packed.shape[0]
+    out = np.empty((N, K), np.int8)
+    _L().orc_unpack_int4(_p(packed), N, K, _p(out))
+    return out
+
+
+def gemm_i32(qx, qw):
+    qx, qw = _c(qx, np.int8), _c(qw, np.int8)
+    M, K = qx.shape
+    N = qw.shape[0]
+    assert qw.shape[1] == K
+    acc = np.empty((M, N), np.int32)
+    _L().orc_gemm_i32(_p(qx), _p(qw), M, N, K, _p(acc))
+    return acc
+
+
+def gemm_i64(qx, qw):
+    qx, qw = _c(qx, np.int8), _c(qw, np.int8)
+    M, K = qx.shape
+    N = qw.shape[0]
+    acc = np.empty((M, N), np.int64)
+    _L().orc_gemm_i64(_p(qx), _p(qw), M, N, K, _p(acc))
+    return acc
+
+
+def epilogue(acc, sx, sw, bias=None, epi=EPI_NONE):
+    """y = acc * sx[m] * sw[n] + bias[n], optional GELU; returns float64 [M, N]."""
+    acc = _c(acc, np.int32)
+    sx, sw = _c(sx, np.float32), _c(sw, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    M, N = acc.shape
+    y = np.empty((M, N), np.float64)
+    _L().orc_epilogue_f64(_p(acc), _p(sx), _p(sw), _p(bias), int(epi), M, N, _p(y))
+    return y
+
+
+def round_f32(y):
+    y = _c(y, np.float64)
+    out = np.empty(y.shape, np.float32)
+    _L().orc_round_to_f32(_p(y), y.size, _p(out))
+    return out
+
+
+def round_bf16_bits(y):
+    y = _c(y, np.float64)
+    out = np.empty(y.shape, np.uint16)
+    _L().orc_round_to_bf16(_p(y), y.size, _p(out))
+    return out
+
+
+def bf16_bits_to_f64(bits):
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    bits = np.asarray(bits, np.uint16)
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def qlinear(X, qw, sw, bias=None, epi=EPI_NONE):
+    """Whole quantized linear.  X float32 or uint16(bf16 bits) [M, K]; qw int8 codes [N, K].
+
+    Returns dict(qx, sx, acc, y) with y in float64 before the single output rounding.
+    """
+    x_is_bf16 = X.dtype == np.uint16
+    X = _c(X, np.uint16 if x_is_bf16 else np.float32)
+    qw, sw = _c(qw, np.int8), _c(sw, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    M, K = X.shape
+    N = qw.shape[0]
+    assert qw.shape[1] == K and sw.shape[0] == N
+    qx = np.empty((M, K), np.int8)
+    sx = np.empty((M,), np.float32)
+    acc = np.empty((M, N), np.int32)
+    y = np.empty((M, N), np.float64)
+    _L().orc_qlinear(_p(X), int(x_is_bf16), M, K, _p(qw), _p(sw), N, _p(bias), int(epi), _p(qx),
+                     _p(sx), _p(acc), _p(y))
+    return {"qx": qx, "sx": sx, "acc": acc, "y": y}
+
+
+def latent_delta(cur, prev):
+    """(sum|cur-prev|, sum|prev|, ratio) in float64."""
+    cur, prev = _c(cur, np.float32).ravel(), _c(prev, np.float32).ravel()
+    assert cur.size == prev.size
+    out = np.empty(3, np.float64)
+    _L().orc_latent_delta(_p(cur), _p(prev), cur.size, _p(out))
+    return out

@@ -1,0 +1,351 @@
+"""Pins for the CPU oracle: every check here compares it with something that is NOT
+the oracle's own formula -- exact rational arithmetic, closed forms, invariants,
+special cases that reduce to a textbook or library routine, brute force.
+
+The paper (arxiv 2503.06545) prints no worked numeric example for its quantizer
+(Section 3.1, Eq. (3)-(4)) or its divergence score (Section 3.2, Eq. (5)), so there
+are no printed values to store; the pins are what the mathematics fixes.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+
+F32_MANT = 24
+
+
+def round_fraction_to_f32(fr: Fraction) -> float:
+    """Correctly rounded (nearest, ties to even) binary32 value of an exact rational.
+
+    Integer arithmetic only; independent of the C compiler's division.
+    Assumes the result is a normal number (true for every use below).
+    """
+    if fr == 0:
+        return 0.0
+    sign = -1 if fr < 0 else 1
+    fr = abs(fr)
+    e = fr.numerator.bit_length() - fr.denominator.bit_length()
+    # find e with 2^e <= fr < 2^(e+1)
+    if Fraction(2) ** e > fr:
+        e -= 1
+    if Fraction(2) ** (e + 1) <= fr:
+        e += 1
+    scaled = fr / Fraction(2) ** (e - (F32_MANT - 1))  # in [2^23, 2^24)
+    fl = scaled.numerator // scaled.denominator
+    rem = scaled - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (fl & 1)):
+        fl += 1
+    assert -126 <= e <= 127
+    return sign * float(Fraction(fl) * Fraction(2) ** (e - (F32_MANT - 1)))
+
+
+def rne_int(fr: Fraction) -> int:
+    fl = math.floor(fr)
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (fl & 1)):
+        fl += 1
+    return int(fl)
+
+
+def exact_quant_row(x: np.ndarray, qmax: int):
+    """The quantizer's definition evaluated with exact rationals + explicit roundings."""
+    xs = [Fraction(float(v)) for v in x]
+    a = max(abs(v) for v in xs) if xs else Fraction(0)
+    a = max(a, Fraction(2) ** -64)
+    s = round_fraction_to_f32(a / qmax)
+    q = []
+    for v in xs:
+        t = round_fraction_to_f32(v / Fraction(s)) if v != 0 else 0.0
+        q.append(int(min(max(rne_int(Fraction(t)), -qmax), qmax)))
+    return np.array(q, np.int8), np.float32(s)
+
+
+def test_round_helper_matches_numpy_cast():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        a, b = rng.standard_normal(2)
+        fr = Fraction(float(a)) / Fraction(float(b))
+        assert round_fraction_to_f32(fr) == float(np.float32(float(a) / float(b)))
+
+
+# ------------------------------------------------------------------ quantizer
+
+@pytest.mark.parametrize("qmax", [127, 7])
+def test_quantizer_against_exact_rational_brute_force(qmax):
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((6, 8)).astype(np.float32)
+    X[1] *= 1e-3
+    X[2] *= 1e4
+    X[3, 2] = 20.0
+    q, s = oracle._quant_rows(X, qmax)
+    for r in range(X.shape[0]):
+        qe, se = exact_quant_row(X[r], qmax)
+        assert s[r].view(np.uint32) == se.view(np.uint32)
+        assert np.array_equal(q[r], qe)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_scale_is_symmetrised_range_over_levels(bits):
+    """Eq. (4) on the symmetrised range [-a, a] with the lowest level unused:
+    s = 2a / (2^b - 2), which is a / (2^(b-1) - 1)."""
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((16, 32)).astype(np.float32)
+    _, s = oracle.quant_weight(W, bits)
+    for n in range(W.shape[0]):
+        a = Fraction(float(np.abs(W[n]).max()))
+        expect = round_fraction_to_f32(2 * a / (2 ** bits - 2))
+        assert float(s[n]) == expect
+
+
+@pytest.mark.parametrize("qmax", [127, 7])
+def test_fp64_brute_force_agrees_away_from_ties(qmax):
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((64, 96)).astype(np.float32)
+    q, s = oracle._quant_rows(X, qmax)
+    a = np.abs(X.astype(np.float64)).max(axis=1, keepdims=True)
+    t = X.astype(np.float64) / (a / qmax)
+    near_tie = np.abs(np.abs(t - np.floor(t)) - 0.5) < 1e-4
+    ref = np.clip(np.rint(t), -qmax, qmax)
+    assert near_tie.mean() < 0.01
+    assert np.array_equal(q[~near_tie], ref[~near_tie].astype(np.int8))
+
+
+@pytest.mark.parametrize("qmax", [127, 7])
+def test_half_step_invariant_and_full_range(qmax):
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((128, 1152)).astype(np.float32)
+    X[:, [3, 700]] *= 20
+    q, s = oracle._quant_rows(X, qmax)
+    err = np.abs(X.astype(np.float64) - q.astype(np.float64) * s.astype(np.float64)[:, None])
+    assert np.all(err <= 0.5 * s.astype(np.float64)[:, None] * (1 + 2.0 ** -22))
+    assert np.all(np.abs(q.astype(np.int32)).max(axis=1) == qmax)
+    assert np.abs(q.astype(np.int32)).max() <= qmax
+
+
+def test_integer_rows_with_power_of_two_scale_are_reproduced_exactly():
+    rng = np.random.default_rng(11)
+    for j in (-5, 0, 3):
+        ints = rng.integers(-127, 128, size=(8, 64)).astype(np.float32)
+        ints[:, 0] = 127
+        q, s = oracle.quant_act(ints * np.float32(2.0 ** j))
+        assert np.all(s == np.float32(2.0 ** j))
+        assert np.array_equal(q, ints.astype(np.int8))
+    ints = rng.integers(-7, 8, size=(8, 64)).astype(np.float32)
+    ints[:, 5] = -7
+    q, s = oracle.quant_weight(ints, 4)
+    assert np.all(s == 1.0) and np.array_equal(q, ints.astype(np.int8))
+
+
+def test_ties_round_to_even_and_clamp_is_symmetric():
+    x = np.array([[127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, -126.5, 125.5]], np.float32)
+    q, s = oracle.quant_act(x)
+    assert s[0] == 1.0
+    assert q[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 126, -126, 126]
+    # 4-bit: same rule on [-7, 7]; -8 is never produced
+    w = np.array([[7, -7, 6.5, -6.5, 5.5, -0.5, 3.5, -3.5]], np.float32)
+    q, s = oracle.quant_weight(w, 4)
+    assert s[0] == 1.0 and q[0].tolist() == [7, -7, 6, -6, 6, 0, 4, -4]
+
+
+def test_odd_symmetry_and_power_of_two_equivariance():
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((16, 200)).astype(np.float32)
+    q, s = oracle.quant_act(X)
+    qn, sn = oracle.quant_act(-X)
+    assert np.array_equal(qn, -q) and np.array_equal(sn.view(np.uint32), s.view(np.uint32))
+    for j in (-20, 9):
+        q2, s2 = oracle.quant_act(X * np.float32(2.0 ** j))
+        assert np.array_equal(q2, q)
+        assert np.array_equal(s2, s * np.float32(2.0 ** j))
+
+
+def test_zero_and_tiny_rows_use_the_absmax_floor():
+    X = np.zeros((2, 16), np.float32)
+    X[1, 3] = 2.0 ** -80
+    q, s = oracle.quant_act(X)
+    floor_scale = np.float32(2.0 ** -64) / np.float32(127)
+    assert s[0] == floor_scale and s[1] == floor_scale
+    assert not q.any()
+    assert np.isfinite(s).all()
+
+
+def test_bf16_rows_are_read_exactly():
+    rng = np.random.default_rng(17)
+    bits = rng.integers(0, 2 ** 16, size=(32, 128)).astype(np.uint16)
+    bits[(bits & 0x7F80) == 0x7F80] = 0x3F80  # no Inf / NaN
+    as_f32 = (bits.astype(np.uint32) << 16).view(np.float32)
+    qb, sb = oracle.quant_act(bits)
+    qf, sf = oracle.quant_act(as_f32)
+    assert np.array_equal(qb, qf) and np.array_equal(sb.view(np.uint32), sf.view(np.uint32))
+
+
+# ------------------------------------------------------------------ int4 container
+
+def test_int4_container_every_nibble_both_positions():
+    vals = np.arange(-8, 8, dtype=np.int8)
+    codes = np.array([[a, b] for a in vals for b in vals], np.int8).reshape(16, 32)
+    packed = oracle.pack_int4(codes)
+    assert packed.shape == (16, 16)
+    # explicit layout: even k in the low nibble, odd k in the high nibble, two's complement
+    for n in range(16):
+        for j in range(16):
+            lo, hi = int(codes[n, 2 * j]) & 0xF, int(codes[n, 2 * j + 1]) & 0xF
+            assert packed[n, j] == (lo | (hi << 4))
+    assert oracle.pack_int4(np.array([[1, -2]], np.int8))[0, 0] == 0xE1
+    assert np.array_equal(oracle.unpack_int4(packed, 32), codes)
+    with pytest.raises(ValueError):
+        oracle.pack_int4(np.zeros((2, 3), np.int8))
+
+
+# ------------------------------------------------------------------ integer GEMM
+
+def test_gemm_is_exact_against_int64_and_numpy():
+    rng = np.random.default_rng(19)
+    qx = rng.integers(-127, 128, size=(9, 130)).astype(np.int8)
+    qw = rng.integers(-127, 128, size=(7, 130)).astype(np.int8)
+    acc = oracle.gemm_i32(qx, qw)
+    assert np.array_equal(acc.astype(np.int64), oracle.gemm_i64(qx, qw))
+    assert np.array_equal(acc.astype(np.int64), qx.astype(np.int64) @ qw.astype(np.int64).T)
+    # python-int brute force on a corner
+    for m, n in ((0, 0), (8, 6), (3, 2)):
+        assert int(acc[m, n]) == sum(int(a) * int(b) for a, b in zip(qx[m], qw[n]))
+
+
+def test_gemm_extreme_values_do_not_wrap_at_largest_k():
+    K = 4608
+    qx = np.full((2, K), 127, np.int8)
+    qx[1] = -127
+    qw = np.full((2, K), 127, np.int8)
+    qw[1, ::2] = -127
+    acc = oracle.gemm_i32(qx, qw)
+    assert acc[0, 0] == 127 * 127 * K and acc[1, 0] == -127 * 127 * K and acc[0, 1] == 0
+
+
+def test_gemm_k_permutation_invariance_and_one_hot():
+    rng = np.random.default_rng(23)
+    qx = rng.integers(-127, 128, size=(5, 64)).astype(np.int8)
+    qw = rng.integers(-127, 128, size=(6, 64)).astype(np.int8)
+    perm = rng.permutation(64)
+    assert np.array_equal(oracle.gemm_i32(qx, qw), oracle.gemm_i32(qx[:, perm], qw[:, perm]))
+    onehot = np.zeros((64, 64), np.int8)
+    onehot[np.arange(64), np.arange(64)] = 1
+    assert np.array_equal(oracle.gemm_i32(onehot, qw), qw.T.astype(np.int32))
+
+
+# ------------------------------------------------------------------ epilogue
+
+def test_epilogue_equals_textbook_matmul_of_dequantized_operands():
+    rng = np.random.default_rng(29)
+    X = rng.standard_normal((12, 96)).astype(np.float32)
+    W = (rng.standard_normal((10, 96)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(10) * 0.01).astype(np.float32)
+    qw, sw = oracle.quant_weight(W, 8)
+    out = oracle.qlinear(X, qw, sw, b)
+    xdq = out["qx"].astype(np.float64) * out["sx"].astype(np.float64)[:, None]
+    wdq = qw.astype(np.float64) * sw.astype(np.float64)[:, None]
+    ref = xdq @ wdq.T + b.astype(np.float64)
+    assert np.allclose(out["y"], ref, rtol=1e-12, atol=1e-15)
+    # without bias the bias term is really absent
+    out0 = oracle.qlinear(X, qw, sw, None)
+    assert np.allclose(out0["y"], xdq @ wdq.T, rtol=1e-12, atol=1e-15)
+    # transposition / scale indexing: scaling one weight row scales one output column only
+    assert out["y"].shape == (12, 10)
+
+
+def test_gelu_forms_against_libm_and_known_values():
+    acc = np.arange(-40, 41, dtype=np.int32).reshape(1, -1)
+    sx, sw = np.array([0.125], np.float32), np.ones(81, np.float32)
+    v = acc[0].astype(np.float64) * 0.125
+    yt = oracle.epilogue(acc, sx, sw, None, oracle.EPI_GELU_TANH)[0]
+    ye = oracle.epilogue(acc, sx, sw, None, oracle.EPI_GELU_ERF)[0]
+    ref_t = [0.5 * t * (1 + math.tanh(math.sqrt(2 / math.pi) * (t + 0.044715 * t ** 3))) for t in v]
+    ref_e = [0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in v]
+    assert np.allclose(yt, ref_t, rtol=1e-13, atol=1e-16)
+    assert np.allclose(ye, ref_e, rtol=1e-13, atol=1e-16)
+    i1 = list(v).index(1.0)
+    assert abs(ye[i1] - 0.8413447460685429) < 1e-15       # Phi(1)
+    assert abs(yt[i1] - 0.8411919906082768) < 1e-12
+    assert yt[list(v).index(0.0)] == 0 and ye[list(v).index(0.0)] == 0
+    assert abs(ye[-1] - 5.0) < 1e-5 and abs(ye[0]) < 1e-5  # identity / zero in the tails
+
+
+def test_whole_linear_closed_form_on_integers():
+    """Integer X and W with row absmax exactly 127 (or 7): both scales are 1, quantization
+    is the identity and y = X W^T + b exactly."""
+    rng = np.random.default_rng(31)
+    for bits, qm in ((8, 127), (4, 7)):
+        X = rng.integers(-127, 128, size=(20, 48)).astype(np.float32)
+        X[:, 1] = 127
+        W = rng.integers(-qm, qm + 1, size=(14, 48)).astype(np.float32)
+        W[:, 7] = -qm
+        b = rng.integers(-5, 6, size=14).astype(np.float32)
+        qw, sw = oracle.quant_weight(W, bits)
+        out = oracle.qlinear(X, qw, sw, b)
+        assert np.all(sw == 1) and np.all(out["sx"] == 1)
+        assert np.array_equal(out["y"], X.astype(np.float64) @ W.astype(np.float64).T + b)
+
+
+def test_output_rounding_to_bf16_is_nearest_even():
+    import torch
+    cases = np.array([1.0, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, -2.5,
+                      3.14159, 65280.0, 1e-30, 0.0])
+    bits = oracle.round_bf16_bits(cases)
+    assert bits[0] == 0x3F80 and bits[1] == 0x3F80 and bits[2] == 0x3F82 and bits[3] == 0x3F81
+    rng = np.random.default_rng(37)
+    y = rng.standard_normal(4096) * 10.0 ** rng.integers(-3, 4, 4096)
+    got = oracle.round_bf16_bits(y)
+    ref = torch.from_numpy(y.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy()
+    assert np.array_equal(got.view(np.int16), ref)
+    assert np.array_equal(oracle.round_f32(y), y.astype(np.float32))
+
+
+def test_quantization_noise_is_small_and_grows_at_4_bits():
+    rng = np.random.default_rng(41)
+    X = rng.standard_normal((64, 1152)).astype(np.float32)
+    W = (rng.standard_normal((96, 1152)) * 0.02).astype(np.float32)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    errs = {}
+    for bits in (8, 4):
+        qw, sw = oracle.quant_weight(W, bits)
+        y = oracle.qlinear(X, qw, sw)["y"]
+        errs[bits] = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    assert errs[8] < 0.03 and errs[8] < errs[4] < 0.3
+
+
+# ------------------------------------------------------------------ latent delta
+
+def test_latent_delta_closed_forms():
+    rng = np.random.default_rng(43)
+    b = rng.standard_normal(10007).astype(np.float32)
+    num, den, rel = oracle.latent_delta(b, b)
+    assert num == 0 and rel == 0 and den == math.fsum(abs(float(v)) for v in b)
+    # cur = 0.5 * prev and cur = 3 * prev on 12-bit values are exact in binary32
+    num, den, rel = oracle.latent_delta(b * np.float32(0.5), b)
+    assert abs(num - 0.5 * den) <= 1e-12 * den and abs(rel - 0.5) < 1e-12
+    b12 = np.round(b * 512).astype(np.float32) / np.float32(512)
+    num, den, rel = oracle.latent_delta(b12 * np.float32(3), b12)
+    assert abs(num - 2 * den) <= 1e-12 * den and abs(rel - 2.0) < 1e-12
+    # constant offset on an integer grid: every term is exactly c
+    ints = rng.integers(-100, 100, size=5000).astype(np.float32)
+    num, den, rel = oracle.latent_delta(ints + np.float32(3.0), ints)
+    assert num == 3.0 * 5000 and den == np.abs(ints).sum(dtype=np.float64)
+    # prev first / cur second matters for the denominator
+    a = np.array([1, 2, 3], np.float32)
+    z = np.zeros(3, np.float32)
+    assert oracle.latent_delta(a, z)[2] == math.inf and oracle.latent_delta(z, z)[2] == 0
+    assert oracle.latent_delta(z, a)[2] == 1.0
+
+
+def test_latent_delta_against_compensated_sum():
+    rng = np.random.default_rng(47)
+    prev = rng.standard_normal(200003).astype(np.float32)
+    cur = (prev + 1e-2 * rng.standard_normal(200003)).astype(np.float32)
+    num, den, rel = oracle.latent_delta(cur, prev)
+    rn = math.fsum(abs(float(a) - float(b)) for a, b in zip(cur, prev))
+    rd = math.fsum(abs(float(b)) for b in prev)
+    assert abs(num - rn) <= 1e-11 * rn and abs(den - rd) <= 1e-11 * rd
+    assert abs(rel - rn / rd) <= 1e-11 * rel
+    assert 0.008 < rel < 0.012
