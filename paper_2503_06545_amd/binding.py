@@ -1,0 +1,247 @@
+"""ctypes binding of libqc.so: argument marshalling only.
+
+The functions named like the C entry points take raw device addresses (ints), exactly as
+``include/qc.h`` declares them.  The ``*_t`` helpers take torch tensors, which here are
+nothing but device memory and a stream; every arithmetic step runs inside libqc's kernels.
+There is no fallback: if the library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqc.so")
+
+QC_OK, QC_ERR_INVALID_ARG, QC_ERR_UNSUPPORTED, QC_ERR_WORKSPACE, QC_ERR_DEVICE = range(5)
+QC_F32, QC_BF16 = 0, 1
+QC_EPI_NONE, QC_EPI_GELU_TANH, QC_EPI_GELU_ERF = 0, 1, 2
+QC_OUT_F32, QC_OUT_BF16, QC_OUT_I32_ACC = 0, 1, 2
+QC_MAX_K = 131072
+
+EXPORTS = (
+    "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",
+    "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
+    "qc_qlinear", "qc_debug_workspace_act", "qc_latent_delta", "qc_latent_delta_workspace_init",
+)
+
+
+class QcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libqc.so (built in-tree by ``paper_2503_06545_amd.build``).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2503_06545_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        L.qc_status_string.restype = ctypes.c_char_p
+        L.qc_status_string.argtypes = [i32]
+        L.qc_version.restype = i32
+        L.qc_version.argtypes = []
+        L.qc_packed_weight_bytes.restype = sz
+        L.qc_packed_weight_bytes.argtypes = [i64, i64, i32]
+        L.qc_qlinear_workspace_bytes.restype = sz
+        L.qc_qlinear_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qc_latent_delta_workspace_bytes.restype = sz
+        L.qc_latent_delta_workspace_bytes.argtypes = [i64]
+        L.qc_pack_weight.restype = i32
+        L.qc_pack_weight.argtypes = [vp, i64, i64, i32, vp, vp, vp]
+        L.qc_unpack_weight_codes.restype = i32
+        L.qc_unpack_weight_codes.argtypes = [vp, i64, i64, i32, vp, vp]
+        L.qc_quant_act.restype = i32
+        L.qc_quant_act.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+        L.qc_qlinear.restype = i32
+        L.qc_qlinear.argtypes = [vp, i32, i64, i64, vp, vp, i32, i64, vp, i32, vp, i32, vp, sz, vp]
+        L.qc_debug_workspace_act.restype = i32
+        L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
+        L.qc_latent_delta.restype = i32
+        L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+        L.qc_latent_delta_workspace_init.restype = i32
+        L.qc_latent_delta_workspace_init.argtypes = [vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+# ---- the C entry points, same names, raw addresses ---------------------------------------
+
+def status_string(status: int) -> str:
+    return lib().qc_status_string(int(status)).decode()
+
+
+def qc_version() -> int:
+    return int(lib().qc_version())
+
+
+def qc_packed_weight_bytes(N: int, K: int, bits: int) -> int:
+    return int(lib().qc_packed_weight_bytes(N, K, bits))
+
+
+def qc_qlinear_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().qc_qlinear_workspace_bytes(M, K, N))
+
+
+def qc_latent_delta_workspace_bytes(n: int) -> int:
+    return int(lib().qc_latent_delta_workspace_bytes(n))
+
+
+def qc_pack_weight(W, N, K, bits, packed, w_scale, stream=0) -> int:
+    return int(lib().qc_pack_weight(W, N, K, bits, packed, w_scale, stream))
+
+
+def qc_unpack_weight_codes(packed, N, K, bits, codes, stream=0) -> int:
+    return int(lib().qc_unpack_weight_codes(packed, N, K, bits, codes, stream))
+
+
+def qc_quant_act(X, xdt, M, K, qx, x_scale, stream=0) -> int:
+    return int(lib().qc_quant_act(X, xdt, M, K, qx, x_scale, stream))
+
+
+def qc_qlinear(X, xdt, M, K, packed, w_scale, bits, N, bias, epi, Y, ydt, workspace,
+               workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear(X, xdt, M, K, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                                workspace, workspace_bytes, stream))
+
+
+def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
+    return int(lib().qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream))
+
+
+def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream))
+
+
+def qc_latent_delta_workspace_init(workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_latent_delta_workspace_init(workspace, workspace_bytes, stream))
+
+
+# ---- tensor helpers: allocate outputs with torch, pass addresses and the current stream ----
+
+def _torch():
+    import torch
+    return torch
+
+
+def _stream() -> int:
+    return int(_torch().cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != QC_OK:
+        raise QcError(status, where)
+
+
+def _xdt(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return QC_F32
+    if t.dtype == torch.bfloat16:
+        return QC_BF16
+    raise TypeError(f"activations must be float32 or bfloat16, got {t.dtype}")
+
+
+EPI = {"none": QC_EPI_NONE, "gelu_tanh": QC_EPI_GELU_TANH, "gelu_erf": QC_EPI_GELU_ERF}
+OUT = {"f32": QC_OUT_F32, "bf16": QC_OUT_BF16, "i32": QC_OUT_I32_ACC}
+
+
+class PackedWeight:
+    """Device blob written by qc_pack_weight plus its per-channel scales."""
+
+    def __init__(self, blob, scale, N: int, K: int, bits: int):
+        self.blob, self.scale, self.N, self.K, self.bits = blob, scale, N, K, bits
+
+
+def pack_weight_t(W, bits: int) -> PackedWeight:
+    torch = _torch()
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
+    N, K = W.shape
+    nbytes = qc_packed_weight_bytes(N, K, bits)
+    if nbytes == 0:
+        raise QcError(QC_ERR_UNSUPPORTED, "qc_packed_weight_bytes")
+    blob = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    scale = torch.empty(N, dtype=torch.float32, device=W.device)
+    _check(qc_pack_weight(W.data_ptr(), N, K, bits, blob.data_ptr(), scale.data_ptr(), _stream()),
+           "qc_pack_weight")
+    return PackedWeight(blob, scale, N, K, bits)
+
+
+def unpack_weight_codes_t(pw: PackedWeight):
+    torch = _torch()
+    codes = torch.empty((pw.N, pw.K), dtype=torch.int8, device=pw.blob.device)
+    _check(qc_unpack_weight_codes(pw.blob.data_ptr(), pw.N, pw.K, pw.bits, codes.data_ptr(),
+                                  _stream()), "qc_unpack_weight_codes")
+    return codes
+
+
+def quant_act_t(X):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2
+    M, K = X.shape
+    qx = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    sx = torch.empty(M, dtype=torch.float32, device=X.device)
+    _check(qc_quant_act(X.data_ptr(), _xdt(X), M, K, qx.data_ptr(), sx.data_ptr(), _stream()),
+           "qc_quant_act")
+    return qx, sx
+
+
+def qlinear_workspace_t(M: int, K: int, N: int, device="cuda"):
+    torch = _torch()
+    nbytes = qc_qlinear_workspace_bytes(M, K, N)
+    if nbytes == 0:
+        raise QcError(QC_ERR_UNSUPPORTED, "qc_qlinear_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=None, Y=None):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == pw.K
+    M, K = X.shape
+    if workspace is None:
+        workspace = qlinear_workspace_t(M, K, pw.N, X.device)
+    if Y is None:
+        ydtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[out]
+        Y = torch.empty((M, pw.N), dtype=ydtype, device=X.device)
+    _check(qc_qlinear(X.data_ptr(), _xdt(X), M, K, pw.blob.data_ptr(), pw.scale.data_ptr(), pw.bits,
+                      pw.N, None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
+                      OUT[out], workspace.data_ptr(), workspace.numel(), _stream()), "qc_qlinear")
+    return Y
+
+
+def debug_workspace_act_t(workspace, M: int, K: int):
+    torch = _torch()
+    qx = torch.empty((M, K), dtype=torch.int8, device=workspace.device)
+    sx = torch.empty(M, dtype=torch.float32, device=workspace.device)
+    _check(qc_debug_workspace_act(workspace.data_ptr(), M, K, qx.data_ptr(), sx.data_ptr(),
+                                  _stream()), "qc_debug_workspace_act")
+    return qx, sx
+
+
+def latent_delta_workspace_t(n: int, device="cuda"):
+    """Workspace with its control words zeroed by the library's own fill kernel."""
+    torch = _torch()
+    ws = torch.empty(qc_latent_delta_workspace_bytes(n), dtype=torch.uint8, device=device)
+    _check(qc_latent_delta_workspace_init(ws.data_ptr(), ws.numel(), _stream()),
+           "qc_latent_delta_workspace_init")
+    return ws
+
+
+def latent_delta_t(cur, prev, workspace=None, out3=None):
+    torch = _torch()
+    assert cur.is_cuda and cur.dtype == torch.float32 and cur.is_contiguous()
+    assert prev.shape == cur.shape and prev.dtype == torch.float32 and prev.is_contiguous()
+    n = cur.numel()
+    if workspace is None:
+        workspace = latent_delta_workspace_t(n, cur.device)
+    if out3 is None:
+        out3 = torch.empty(3, dtype=torch.float32, device=cur.device)
+    _check(qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n, out3.data_ptr(), workspace.data_ptr(),
+                           workspace.numel(), _stream()), "qc_latent_delta")
+    return out3

@@ -1,0 +1,66 @@
+// C ABI entry points for activation quantization and the fused quantized linear: argument
+// checks first, then launches on the caller's stream.  Nothing here allocates or synchronises.
+#include "qc_internal.h"
+
+using namespace qc;
+
+namespace {
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+}  // namespace
+
+extern "C" const char *qc_status_string(qc_status status) {
+    switch (status) {
+        case QC_OK: return "QC_OK";
+        case QC_ERR_INVALID_ARG: return "QC_ERR_INVALID_ARG: null or misaligned pointer, bad size or enum";
+        case QC_ERR_UNSUPPORTED: return "QC_ERR_UNSUPPORTED: size or combination not implemented";
+        case QC_ERR_WORKSPACE: return "QC_ERR_WORKSPACE: workspace too small";
+        case QC_ERR_DEVICE: return "QC_ERR_DEVICE: the HIP runtime refused a launch";
+    }
+    return "unknown qc_status";
+}
+
+extern "C" int qc_version(void) { return 1000; }
+
+extern "C" size_t qc_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (M < 1 || K < 1 || N < 1 || K > QC_MAX_K) return 0;
+    return act_workspace(M, K).total_bytes;
+}
+
+extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
+                                  float *x_scale, void *stream) {
+    if (!X || !qx || !x_scale || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
+    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                const void *packed, const float *w_scale, int bits, int64_t N,
+                                const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
+        return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
+        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    const int64_t tiles = (ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN);
+    if (tiles > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+
+    uint8_t *base = (uint8_t *)workspace;
+    float *x_scale = (float *)base;
+    uint8_t *x_tiled = base + ws.scale_bytes;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, x_tiled, ws.KF, x_scale, s);
+    if (e != hipSuccess) return QC_ERR_DEVICE;
+    e = launch_gemm(x_tiled, x_scale, (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
+                    ydt, s);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}

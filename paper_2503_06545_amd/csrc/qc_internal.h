@@ -1,0 +1,77 @@
+// Internal declarations shared by the libqc translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qc.h"
+
+namespace qc {
+
+// ---- data layout of the GEMM operands in HBM -------------------------------------------
+//
+// Both GEMM operands are stored as "fragments": the 1 KiB a 64-lane wavefront hands to one
+// v_mfma_i32_32x32x32_i8 as its A or B operand, lane after lane (lane l supplies 16
+// consecutive k of row l % 32, k half l / 32).  A fragment therefore covers 32 rows x 32 k,
+// and a wavefront moves it HBM -> LDS -> registers with fully linear 16 B/lane accesses.
+//
+//   fragment index   = (row / 32) * KF + k / 32          KF = Kp / 32, Kp = K rounded up to 64
+//   byte in fragment = (((k % 32) / 16) * 32 + row % 32) * 16 + k % 16
+//
+// Activations use their token index as `row`.  Weights use a permuted row index p so that a
+// lane of the GEMM ends up holding 8 consecutive output channels (one 16 B bf16 store):
+// inside each group of 64 channels, channel n = 64 G + r sits at
+//   p = 64 G + 32 * ((r / 4) % 2) + 8 * (r / 16) + 4 * ((r / 8) % 2) + r % 4.
+// 4-bit weights keep the same (p, k) -> lane mapping but one 1 KiB unit spans 64 k: lane l
+// holds 8 bytes of nibbles for the even 32-k fragment and 8 bytes for the odd one.  Inside a
+// dword of 8 nibbles, k offset e (0..7) sits in nibble (e < 4 ? 2 e : 2 (e - 4) + 1), so that
+// (v << 4) & 0xF0F0F0F0 and v & 0xF0F0F0F0 are the int8 operand dwords (codes times 16).
+
+constexpr int kFragRows = 32;
+constexpr int kFragK = 32;
+constexpr int kFragBytes = 1024;
+constexpr int kKAlign = 64;        // K is padded to this (one pipeline stage of the GEMM)
+constexpr int kTileM = 256;        // GEMM block tile, tokens
+constexpr int kTileN = 128;        // GEMM block tile, output channels
+constexpr int kPackedHeaderBytes = 256;
+constexpr uint32_t kPackedTag = 0x51433031u;  // "QC01"
+constexpr float kAbsmaxFloor = 0x1p-64f;
+
+__host__ __device__ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+__host__ __device__ inline int64_t frag_offset(int64_t row, int64_t k, int64_t KF) {
+    return ((row / kFragRows) * KF + k / kFragK) * kFragBytes +
+           (((k % kFragK) / 16) * 32 + row % kFragRows) * 16 + k % 16;
+}
+
+__host__ __device__ inline int64_t weight_row_of_channel(int64_t n) {
+    int64_t r = n % 64;
+    return (n - r) + 32 * ((r / 4) % 2) + 8 * (r / 16) + 4 * ((r / 8) % 2) + r % 4;
+}
+
+// workspace of qc_qlinear: [ x_scale: Mp floats ][ tiled codes: Mp * Kp bytes ]
+struct ActWorkspace {
+    int64_t Mp, Kp, KF;
+    size_t scale_bytes, total_bytes;
+};
+
+__host__ inline ActWorkspace act_workspace(int64_t M, int64_t K) {
+    ActWorkspace w;
+    w.Mp = round_up(M, kTileM);
+    w.Kp = round_up(K, kKAlign);
+    w.KF = w.Kp / kFragK;
+    w.scale_bytes = (size_t)round_up(w.Mp * 4, 256);
+    w.total_bytes = w.scale_bytes + (size_t)w.Mp * (size_t)w.Kp;
+    return w;
+}
+
+// ---- launchers (each returns hipGetLastError() of its launch) --------------------------
+
+hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx_rowmajor,
+                            uint8_t *qx_tiled, int64_t KF, float *x_scale, hipStream_t stream);
+
+hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8_t *w_packed,
+                       const float *w_scale, const float *bias, void *Y, int64_t M, int64_t N,
+                       int64_t K, int bits, qc_epilogue epi, qc_out ydt, hipStream_t stream);
+
+}  // namespace qc

@@ -1,0 +1,158 @@
+// Offline weight quantization and packing (Section 4.1 "Quantization Scheme": per-channel
+// weights; Section 3.2 AIGQ (1): bit-width chosen per layer), plus the test hooks that turn
+// the library's internal orders back into canonical row-major codes.
+#include "qc_internal.h"
+
+namespace qc {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ inline int weight_code(float w, float s, float qmax) {
+    float r = rintf(w / s);  // IEEE division, ties to even
+    r = fminf(fmaxf(r, -qmax), qmax);
+    return (int)r;
+}
+
+// byte offset (from the start of the code area) of the dword that holds the 8 nibbles of
+// packed row p, k = k8 .. k8 + 7 (k8 a multiple of 8)
+__device__ __host__ inline int64_t w4_dword_offset(int64_t p, int64_t k8, int64_t KF) {
+    const int64_t lane = ((k8 % 32) / 16) * 32 + p % 32;
+    return ((p / 32) * (KF / 2) + k8 / 64) * kFragBytes + lane * 16 + ((k8 % 64) / 32) * 8 +
+           ((k8 % 16) / 8) * 4;
+}
+
+__device__ __host__ inline int w4_nibble_of(int e) { return e < 4 ? 2 * e : 2 * (e - 4) + 1; }
+
+// One wavefront per (padded) output channel.
+__global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__restrict__ W,
+                                                               int64_t N, int64_t K, int bits,
+                                                               uint8_t *__restrict__ blob,
+                                                               float *__restrict__ w_scale,
+                                                               int64_t Np, int64_t Kp) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        uint32_t *h32 = reinterpret_cast<uint32_t *>(blob);
+        h32[0] = kPackedTag;
+        h32[1] = (uint32_t)bits;
+        int64_t *h64 = reinterpret_cast<int64_t *>(blob + 8);
+        h64[0] = N; h64[1] = K; h64[2] = Np; h64[3] = Kp;
+    }
+    if (n >= Np) return;
+    const bool live = n < N;
+    const float *wrow = W + (live ? n : 0) * K;
+    const float qmax = bits == 8 ? 127.0f : 7.0f;
+
+    float a = 0.0f;
+    if (live)
+        for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(wrow[k]));
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    const float s = fmaxf(a, kAbsmaxFloor) / qmax;
+    if (live && lane == 0) w_scale[n] = s;
+
+    uint8_t *codes = blob + kPackedHeaderBytes;
+    const int64_t KF = Kp / kFragK;
+    const int64_t p = weight_row_of_channel(n);
+    for (int64_t k8 = (int64_t)lane * 8; k8 < Kp; k8 += 64 * 8) {
+        int c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            c[e] = (live && k8 + e < K) ? weight_code(wrow[k8 + e], s, qmax) : 0;
+        if (bits == 8) {
+            uint2 out;
+            out.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | ((uint32_t)(c[3] & 0xff) << 24);
+            out.y = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | ((uint32_t)(c[7] & 0xff) << 24);
+            *reinterpret_cast<uint2 *>(codes + frag_offset(p, k8, KF)) = out;
+        } else {
+            uint32_t out = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out |= (uint32_t)(c[e] & 0xf) << (4 * w4_nibble_of(e));
+            *reinterpret_cast<uint32_t *>(codes + w4_dword_offset(p, k8, KF)) = out;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_weight_kernel(const uint8_t *__restrict__ blob,
+                                                                 int64_t N, int64_t K, int bits,
+                                                                 int64_t Kp,
+                                                                 int8_t *__restrict__ out) {
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= N * K) return;
+    const int64_t n = idx / K, k = idx % K;
+    const uint8_t *codes = blob + kPackedHeaderBytes;
+    const int64_t KF = Kp / kFragK;
+    const int64_t p = weight_row_of_channel(n);
+    if (bits == 8) {
+        out[idx] = (int8_t)codes[frag_offset(p, k, KF)];
+    } else {
+        const int64_t k8 = k - k % 8;
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(p, k8, KF));
+        const int nib = (int)((v >> (4 * w4_nibble_of((int)(k % 8)))) & 0xf);
+        out[idx] = (int8_t)(nib >= 8 ? nib - 16 : nib);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void untile_act_kernel(const uint8_t *__restrict__ tiled,
+                                                              const float *__restrict__ scales,
+                                                              int64_t M, int64_t K, int64_t KF,
+                                                              int8_t *__restrict__ qx,
+                                                              float *__restrict__ x_scale) {
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx < M) x_scale[idx] = scales[idx];
+    if (idx >= M * K) return;
+    const int64_t m = idx / K, k = idx % K;
+    qx[idx] = (int8_t)tiled[frag_offset(m, k, KF)];
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+}  // namespace qc
+
+using namespace qc;
+
+extern "C" size_t qc_packed_weight_bytes(int64_t N, int64_t K, int bits) {
+    if ((bits != 4 && bits != 8) || N < 1 || K < 1 || K > QC_MAX_K) return 0;
+    if (bits == 4 && (K % 2)) return 0;
+    const int64_t Np = round_up(N, kTileN), Kp = round_up(K, kKAlign);
+    return (size_t)kPackedHeaderBytes + (size_t)(Np * Kp * bits / 8);
+}
+
+extern "C" qc_status qc_pack_weight(const float *W, int64_t N, int64_t K, int bits, void *packed,
+                                    float *w_scale, void *stream) {
+    if (!W || !packed || !w_scale || N < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (!aligned(W, 16) || !aligned(packed, 256) || !aligned(w_scale, 16)) return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const int64_t Np = round_up(N, kTileN), Kp = round_up(K, kKAlign);
+    const int64_t blocks = Np / (kThreads / 64);
+    pack_weight_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        W, N, K, bits, (uint8_t *)packed, w_scale, Np, Kp);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_unpack_weight_codes(const void *packed, int64_t N, int64_t K, int bits,
+                                            int8_t *codes, void *stream) {
+    if (!packed || !codes || N < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (!aligned(packed, 256)) return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const int64_t Kp = round_up(K, kKAlign);
+    const int64_t blocks = (N * K + kThreads - 1) / kThreads;
+    unpack_weight_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        (const uint8_t *)packed, N, K, bits, Kp, codes);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K,
+                                            int8_t *qx, float *x_scale, void *stream) {
+    if (!workspace || !qx || !x_scale || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (K > QC_MAX_K) return QC_ERR_UNSUPPORTED;
+    if (!aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    const ActWorkspace ws = act_workspace(M, K);
+    const uint8_t *base = (const uint8_t *)workspace;
+    const int64_t blocks = (M * K + kThreads - 1) / kThreads;
+    untile_act_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        base + ws.scale_bytes, (const float *)base, M, K, ws.KF, qx, x_scale);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}

@@ -1,0 +1,182 @@
+// Per-token dynamic activation quantization (Section 4.1 "Quantization Scheme": activation
+// parameters computed online; Section 3.1 Eq. (3)-(4) in symmetric signed form).
+//
+// HBM-bound: every element of X is read once and one int8 code is written.  A row is held in
+// registers between the absmax pass and the cast, so there is no second read.
+#include "qc_internal.h"
+
+namespace qc {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnit = 16;          // elements handled as one unit: 16 codes = one 16 B store
+constexpr int kUnitsPerThread = 9; // a row is spread over TPR lanes, <= 9 units each
+
+__device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// 16 elements of one row, widened to float.
+template <typename XT>
+struct Unit;
+
+template <>
+struct Unit<float> {
+    float4 v[4];
+    __device__ void load(const float *p) {
+        const float4 *q = reinterpret_cast<const float4 *>(p);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = q[i];
+    }
+    __device__ void zero() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __device__ float get(int i) const {
+        const float4 &f = v[i >> 2];
+        switch (i & 3) { case 0: return f.x; case 1: return f.y; case 2: return f.z; default: return f.w; }
+    }
+};
+
+template <>
+struct Unit<uint16_t> {  // bf16 bit patterns
+    uint4 v[2];
+    __device__ void load(const uint16_t *p) {
+        const uint4 *q = reinterpret_cast<const uint4 *>(p);
+        v[0] = q[0];
+        v[1] = q[1];
+    }
+    __device__ void zero() { v[0] = v[1] = make_uint4(0, 0, 0, 0); }
+    __device__ float get(int i) const {
+        const uint4 &u = v[i >> 3];
+        uint32_t w;
+        switch ((i >> 1) & 3) { case 0: w = u.x; break; case 1: w = u.y; break; case 2: w = u.z; break; default: w = u.w; }
+        return (i & 1) ? bf16_hi(w) : bf16_lo(w);
+    }
+};
+
+// code = clamp(rne(x / s), -127, 127): true IEEE division, then round half to even.
+__device__ inline int quant_code(float x, float s) {
+    float r = rintf(x / s);
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+__device__ inline float scale_of(float absmax) { return fmaxf(absmax, kAbsmaxFloor) / 127.0f; }
+
+// TPR lanes share a row; rows per block = 256 / TPR.  Needs K % 16 == 0 and
+// K / 16 <= TPR * kUnitsPerThread.
+template <typename XT, int TPR>
+__global__ __launch_bounds__(kThreads) void quant_rows_kernel(const XT *__restrict__ X, int64_t M,
+                                                              int64_t K, int8_t *__restrict__ qx,
+                                                              uint8_t *__restrict__ qx_tiled,
+                                                              int64_t KF,
+                                                              float *__restrict__ x_scale) {
+    constexpr int kRowsPerBlock = kThreads / TPR;
+    const int sub = threadIdx.x % TPR;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / TPR;
+    const int units = (int)(K / kUnit);
+    const bool live = row < M;
+    const XT *xrow = X + (live ? row : 0) * K;
+
+    Unit<XT> u[kUnitsPerThread];
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = i * TPR + sub;
+        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        else u[i].zero();
+    }
+
+    float a = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i)
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e) a = fmaxf(a, fabsf(u[i].get(e)));
+#pragma unroll
+    for (int d = 1; d < TPR; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+
+    const float s = scale_of(a);
+    if (live && sub == 0) x_scale[row] = s;
+
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = i * TPR + sub;
+        if (!(live && ui < units)) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc |= ((uint32_t)quant_code(u[i].get(d * 4 + b), s) & 0xffu) << (8 * b);
+            w[d] = acc;
+        }
+        const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
+        if (qx) *reinterpret_cast<uint4 *>(qx + row * K + (int64_t)ui * kUnit) = out;
+        if (qx_tiled)
+            *reinterpret_cast<uint4 *>(qx_tiled + frag_offset(row, (int64_t)ui * kUnit, KF)) = out;
+    }
+}
+
+// Any K, any alignment: one wavefront per row, two passes over the row (the second one is
+// served by the caches).  Slow path for shapes the vector kernel does not take.
+template <typename XT>
+__global__ __launch_bounds__(kThreads) void quant_rows_generic_kernel(
+    const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const XT *xrow = X + row * K;
+    auto widen = [](XT v) -> float {
+        if constexpr (sizeof(XT) == 2) return __uint_as_float((uint32_t)v << 16);
+        else return v;
+    };
+    float a = 0.0f;
+    for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(widen(xrow[k])));
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    const float s = scale_of(a);
+    if (lane == 0) x_scale[row] = s;
+    for (int64_t k = lane; k < K; k += 64) {
+        const int8_t c = (int8_t)quant_code(widen(xrow[k]), s);
+        if (qx) qx[row * K + k] = c;
+        if (qx_tiled) qx_tiled[frag_offset(row, k, KF)] = (uint8_t)c;
+    }
+}
+
+template <typename XT>
+hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
+                        int64_t KF, float *x_scale, hipStream_t stream) {
+    const int64_t units = K / kUnit;
+    const bool vec = (K % kUnit == 0) && units <= 64 * kUnitsPerThread;
+    if (!vec) {
+        const int64_t blocks = (M + 3) / 4;
+        quant_rows_generic_kernel<XT><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(
+            X, M, K, qx, qx_tiled, KF, x_scale);
+        return hipGetLastError();
+    }
+#define QC_LAUNCH_TPR(TPR)                                                                   \
+    do {                                                                                     \
+        const int64_t blocks = (M + (kThreads / TPR) - 1) / (kThreads / TPR);                \
+        quant_rows_kernel<XT, TPR><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(   \
+            X, M, K, qx, qx_tiled, KF, x_scale);                                             \
+    } while (0)
+    if (units <= 8 * kUnitsPerThread) QC_LAUNCH_TPR(8);
+    else if (units <= 16 * kUnitsPerThread) QC_LAUNCH_TPR(16);
+    else if (units <= 32 * kUnitsPerThread) QC_LAUNCH_TPR(32);
+    else QC_LAUNCH_TPR(64);
+#undef QC_LAUNCH_TPR
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx_rowmajor,
+                            uint8_t *qx_tiled, int64_t KF, float *x_scale, hipStream_t stream) {
+    if (xdt == QC_BF16)
+        return launch_typed<uint16_t>((const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale,
+                                      stream);
+    return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, stream);
+}
+
+}  // namespace qc

@@ -1,0 +1,86 @@
+"""Host-side checks that need no GPU: the library loads, exports what include/qc.h declares,
+its size queries are right and argument errors are caught before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_06545_amd import binding as qc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "qc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(qc.EXPORTS)
+    lib = ctypes.CDLL(qc.LIB_PATH)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert qc.qc_version() == 1000
+    assert qc.status_string(0) == "QC_OK"
+    for s in range(1, 5):
+        assert qc.status_string(s).startswith("QC_ERR_")
+
+
+def test_size_queries():
+    # int8: padded to 128 channels x 64 k, plus a 256-byte header
+    assert qc.qc_packed_weight_bytes(3456, 1152, 8) == 256 + 3456 * 1152
+    assert qc.qc_packed_weight_bytes(1152, 4608, 4) == 256 + 1152 * 4608 // 2
+    assert qc.qc_packed_weight_bytes(200, 100, 8) == 256 + 256 * 128
+    assert qc.qc_packed_weight_bytes(10, 15, 4) == 0          # odd K with 4 bits
+    assert qc.qc_packed_weight_bytes(10, 16, 5) == 0
+    assert qc.qc_packed_weight_bytes(0, 16, 8) == 0
+    assert qc.qc_packed_weight_bytes(10, qc.QC_MAX_K + 1, 8) == 0
+    assert qc.qc_qlinear_workspace_bytes(16384, 1152, 3456) == 16384 * 4 + 16384 * 1152
+    assert qc.qc_qlinear_workspace_bytes(300, 100, 7) == 512 * 4 + 512 * 128
+    assert qc.qc_qlinear_workspace_bytes(0, 100, 7) == 0
+    assert qc.qc_latent_delta_workspace_bytes(1 << 22) >= 256
+    assert qc.qc_latent_delta_workspace_bytes(0) == 0
+
+
+def test_argument_errors_come_before_any_launch():
+    A = 0x10000  # a fake, aligned, never dereferenced address: every call below must fail first
+    assert qc.qc_quant_act(None, qc.QC_BF16, 4, 16, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_quant_act(A, qc.QC_BF16, 0, 16, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_quant_act(A, 7, 4, 16, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_quant_act(A + 2, qc.QC_BF16, 4, 16, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_quant_act(A, qc.QC_BF16, 4, qc.QC_MAX_K + 1, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_pack_weight(A, 8, 15, 4, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_pack_weight(A, 8, 16, 3, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_pack_weight(A, 8, 16, 8, A + 16, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_pack_weight(A, 8, 16, 8, None, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_unpack_weight_codes(A, 8, 15, 4, A) == qc.QC_ERR_UNSUPPORTED
+    ok = dict(X=A, xdt=qc.QC_BF16, M=4, K=16, packed=A, w_scale=A, bits=8, N=8, bias=None,
+              epi=qc.QC_EPI_NONE, Y=A, ydt=qc.QC_OUT_BF16, workspace=A, workspace_bytes=1 << 30)
+    def call(**kw):
+        return qc.qc_qlinear(**{**ok, **kw})
+    assert call(X=None) == qc.QC_ERR_INVALID_ARG
+    assert call(workspace=None) == qc.QC_ERR_INVALID_ARG
+    assert call(epi=9) == qc.QC_ERR_INVALID_ARG
+    assert call(ydt=9) == qc.QC_ERR_INVALID_ARG
+    assert call(bias=A + 4) == qc.QC_ERR_INVALID_ARG
+    assert call(bits=4, K=15) == qc.QC_ERR_UNSUPPORTED
+    assert call(bits=2) == qc.QC_ERR_UNSUPPORTED
+    assert call(workspace_bytes=16) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_latent_delta(A, A, 0, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_latent_delta(A, A + 4, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_latent_delta(A, A, 8, A, A, 8) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_latent_delta_workspace_init(None, 1024) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_latent_delta_workspace_init(A, 8) == qc.QC_ERR_WORKSPACE
+
+
+def test_missing_library_is_a_loud_error(monkeypatch):
+    monkeypatch.setattr(qc, "_lib", None)
+    monkeypatch.setattr(qc, "LIB_PATH", "/nonexistent/libqc.so")
+    with pytest.raises(ImportError):
+        qc.lib()

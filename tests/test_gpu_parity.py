@@ -1,0 +1,299 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: bit-exact for int8 codes, scales (compared as bit patterns) and int32 accumulators;
+outputs within |y - ref| <= rtol * |ref| + rtol * RMS(ref) with rtol 1e-3 (float output)
+or 2e-2 (bf16 output); latent delta within 1e-5 relative.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2503_06545_amd import binding as qc
+from paper_2503_06545_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL = {"f32": 1e-3, "bf16": 2e-2}
+EPI_ORACLE = {"none": oracle.EPI_NONE, "gelu_tanh": oracle.EPI_GELU_TANH, "gelu_erf": oracle.EPI_GELU_ERF}
+
+
+def dev(a: np.ndarray):
+    """numpy -> device tensor; uint16 arrays are bf16 bit patterns."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def host_f64(y: torch.Tensor) -> np.ndarray:
+    torch.cuda.synchronize()
+    if y.dtype == torch.bfloat16:
+        return oracle.bf16_bits_to_f64(y.view(torch.int16).cpu().numpy().view(np.uint16))
+    return y.cpu().numpy().astype(np.float64)
+
+
+def bits_equal(a: np.ndarray, b: np.ndarray) -> bool:
+    return np.array_equal(np.ascontiguousarray(a).view(np.uint32), np.ascontiguousarray(b).view(np.uint32))
+
+
+def assert_outputs_close(got: np.ndarray, ref: np.ndarray, rtol: float):
+    rms = math.sqrt(float(np.mean(ref ** 2)))
+    err = np.abs(got - ref)
+    bound = rtol * np.abs(ref) + rtol * rms
+    worst = int(np.argmax(err - bound))
+    assert np.all(err <= bound), (
+        f"max violation at flat index {worst}: got {got.flat[worst]} ref {ref.flat[worst]} "
+        f"rms {rms} rtol {rtol}")
+
+
+def random_x(rng, M, K, dtype):
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.integers(0, K, size=max(1, K // 100))] *= 20
+    return synth.to_bf16_bits(x) if dtype == "bf16" else x
+
+
+# ------------------------------------------------------------------ qc_quant_act
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K", [(256, 1152), (300, 4608), (1, 16), (37, 2304), (65, 1000),
+                                 (5, 24), (3, 9216), (2, 10000), (130, 7)])
+def test_quant_act_matches_oracle_bit_for_bit(dtype, M, K):
+    rng = np.random.default_rng(M * 100003 + K)
+    x = random_x(rng, M, K, dtype)
+    x[M // 2] = 0  # a zero row uses the absmax floor
+    q_ref, s_ref = oracle.quant_act(x)
+    qx, sx = qc.quant_act_t(dev(x))
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), s_ref)
+    assert np.array_equal(qx.cpu().numpy(), q_ref)
+
+
+def test_quant_act_tiny_config_and_ties():
+    x = synth.TINY.x()
+    q_ref, s_ref = oracle.quant_act(x)
+    qx, sx = qc.quant_act_t(dev(x))
+    assert bits_equal(sx.cpu().numpy(), s_ref) and np.array_equal(qx.cpu().numpy(), q_ref)
+    # exact half-way cases: scale 1, ties go to even
+    t = np.zeros((2, 16), np.float32)
+    t[0, :10] = [127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5, -126.5, 125.5]
+    t[1] = -t[0]
+    qx, sx = qc.quant_act_t(dev(t))
+    assert sx.cpu().tolist() == [1.0, 1.0]
+    assert qx[0, :10].cpu().tolist() == [127, 0, 2, 2, 0, -2, -2, 126, -126, 126]
+    assert torch.equal(qx[1], -qx[0])
+
+
+# ------------------------------------------------------------------ qc_pack_weight
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K", [(1152, 1152), (200, 136), (1, 2), (129, 72), (64, 4608), (130, 100)])
+def test_pack_weight_codes_and_scales_bit_exact(bits, N, K):
+    rng = np.random.default_rng(N * 7919 + K + bits)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    if N > 2:
+        W[1] = 0
+    q_ref, s_ref = oracle.quant_weight(W, bits)
+    pw = qc.pack_weight_t(dev(W), bits)
+    codes = qc.unpack_weight_codes_t(pw)
+    torch.cuda.synchronize()
+    assert bits_equal(pw.scale.cpu().numpy(), s_ref)
+    assert np.array_equal(codes.cpu().numpy(), q_ref)
+    if bits == 4:  # canonical nibble container round trip of the same codes
+        assert np.array_equal(oracle.unpack_int4(oracle.pack_int4(codes.cpu().numpy()), K), q_ref)
+
+
+def test_pack_int4_all_nibbles_all_positions():
+    """Every 4-bit code at every k position of a 64-k packing unit, K not a multiple of it."""
+    K = 200
+    codes = np.zeros((16, K), np.float32)
+    for n in range(16):
+        codes[n] = [((n + k) % 15) - 7 for k in range(K)]
+        codes[n, 0] = 7  # absmax 7 -> scale 1
+    pw = qc.pack_weight_t(dev(codes), 4)
+    got = qc.unpack_weight_codes_t(pw).cpu().numpy()
+    assert np.all(pw.scale.cpu().numpy() == 1.0)
+    assert np.array_equal(got, codes.astype(np.int8))
+
+
+# ------------------------------------------------------------------ qc_qlinear
+
+def run_linear_case(x, W, b, bits, epi, out, check_acc=True):
+    M, K = x.shape
+    N = W.shape[0]
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi])
+    xd, pw = dev(x), qc.pack_weight_t(dev(W), bits)
+    bd = None if b is None else dev(b)
+    ws = qc.qlinear_workspace_t(M, K, N)
+    y = qc.qlinear_t(xd, pw, bd, epi, out, workspace=ws)
+    qx, sx = qc.debug_workspace_act_t(ws, M, K)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), ref["sx"]), "activation scales differ"
+    assert np.array_equal(qx.cpu().numpy(), ref["qx"]), "activation codes differ"
+    if check_acc:
+        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"]), "int32 accumulators differ"
+    y_ref = ref["y"]
+    if out == "bf16":  # the oracle's single rounding to the output type
+        y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(y_ref))
+    else:
+        y_ref = oracle.round_f32(y_ref).astype(np.float64)
+    assert_outputs_close(host_f64(y), y_ref, RTOL[out])
+    return y
+
+
+def test_qlinear_tiny_config_full_parity():
+    c = synth.TINY
+    run_linear_case(c.x(), c.weight(), c.bias(), 8, "none", "f32")
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("epi", ["none", "gelu_tanh", "gelu_erf"])
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+def test_qlinear_variants(bits, epi, out):
+    rng = np.random.default_rng(bits * 31 + len(epi) + len(out))
+    M, K, N = 512, 1152, 384
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_linear_case(x, W, b, bits, epi, out)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N", [(300, 136, 200), (1, 16, 1), (257, 64, 129), (33, 200, 77),
+                                   (700, 4608, 130), (256, 2, 8), (513, 1000, 260)])
+def test_qlinear_ragged_shapes(bits, M, K, N):
+    rng = np.random.default_rng(M + 3 * K + 5 * N + bits)
+    x = random_x(rng, M, K, "f32")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_linear_case(x, W, b, bits, "none", "f32")
+    run_linear_case(synth.to_bf16_bits(x), W, None, bits, "gelu_tanh", "bf16", check_acc=False)
+
+
+def test_qlinear_closed_form_integers_and_extremes():
+    """Integer operands with unit scales reproduce X W^T + b exactly; all-127 operands reach the
+    largest accumulator magnitude at K = 4608."""
+    rng = np.random.default_rng(5)
+    for bits, qm in ((8, 127), (4, 7)):
+        M, K, N = 64, 4608, 128
+        X = rng.integers(-127, 128, size=(M, K)).astype(np.float32)
+        X[:, 0] = 127
+        W = rng.integers(-qm, qm + 1, size=(N, K)).astype(np.float32)
+        W[:, 1] = qm
+        X[0], W[0] = 127, qm
+        X[1] = -127
+        b = rng.integers(-5, 6, size=N).astype(np.float32)
+        pw = qc.pack_weight_t(dev(W), bits)
+        acc = qc.qlinear_t(dev(X), pw, None, "none", "i32").cpu().numpy()
+        ref = X.astype(np.int64) @ W.astype(np.int64).T
+        assert np.array_equal(acc.astype(np.int64), ref)
+        assert acc[0, 0] == 127 * qm * K and acc[1, 0] == -127 * qm * K
+        y = qc.qlinear_t(dev(X), pw, dev(b), "none", "f32").cpu().numpy().astype(np.float64)
+        assert np.allclose(y, ref + b, rtol=3e-7, atol=0)
+
+
+def test_qlinear_one_hot_rows_return_weight_columns():
+    K, N = 128, 256
+    rng = np.random.default_rng(9)
+    W = rng.integers(-127, 128, size=(N, K)).astype(np.float32)
+    W[:, 0] = 127
+    X = np.zeros((K, K), np.float32)
+    X[np.arange(K), np.arange(K)] = 3.0  # scale 3/127, code 127
+    pw = qc.pack_weight_t(dev(W), 8)
+    acc = qc.qlinear_t(dev(X), pw, None, "none", "i32").cpu().numpy()
+    assert np.array_equal(acc, 127 * W.T.astype(np.int32))
+
+
+def test_qlinear_is_deterministic_and_stays_inside_its_output():
+    rng = np.random.default_rng(11)
+    M, K, N = 777, 1152, 392
+    x = dev(random_x(rng, M, K, "bf16"))
+    pw = qc.pack_weight_t(dev((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), 8)
+    pad = 4096
+    buf = torch.full((M * N + 2 * pad,), -7.0, dtype=torch.bfloat16, device="cuda")
+    Y = buf[pad:pad + M * N].view(M, N)
+    first = qc.qlinear_t(x, pw, None, "none", "bf16", Y=Y).clone()
+    for _ in range(5):
+        again = qc.qlinear_t(x, pw, None, "none", "bf16", Y=Y)
+        assert torch.equal(again.view(torch.int16), first.view(torch.int16))
+    torch.cuda.synchronize()
+    assert torch.all(buf[:pad] == -7.0) and torch.all(buf[pad + M * N:] == -7.0)
+
+
+# ------------------------------------------------------------------ full-size configs, sampled rows
+
+def sampled_rows_case(case: synth.LinearCase, rows_wanted=96):
+    M, K, N = case.M, case.K, case.N
+    x = case.x()
+    W, b = case.weight(), case.bias()
+    pw = qc.pack_weight_t(dev(W), case.bits)
+    ws = qc.qlinear_workspace_t(M, K, N)
+    xd = dev(x)
+    y = qc.qlinear_t(xd, pw, dev(b), case.epi, case.out_dtype, workspace=ws)
+    acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+    qx, sx = qc.debug_workspace_act_t(ws, M, K)
+    torch.cuda.synchronize()
+    rows = synth.sample_rows(M, rows_wanted)
+    ridx = torch.from_numpy(rows).cuda()
+    qw_ref, sw_ref = oracle.quant_weight(W, case.bits)
+    assert bits_equal(pw.scale.cpu().numpy(), sw_ref)
+    assert np.array_equal(qc.unpack_weight_codes_t(pw).cpu().numpy(), qw_ref)
+    # rows are independent under per-token quantization: the oracle runs on the sampled rows
+    ref = oracle.qlinear(x[rows], qw_ref, sw_ref, b, EPI_ORACLE[case.epi])
+    assert bits_equal(sx[ridx].cpu().numpy(), ref["sx"])
+    assert np.array_equal(qx[ridx].cpu().numpy(), ref["qx"])
+    assert np.array_equal(acc[ridx].cpu().numpy(), ref["acc"])
+    y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(ref["y"]))
+    assert_outputs_close(host_f64(y[ridx]), y_ref, RTOL["bf16"])
+    # whole-tensor properties that hold at any size
+    q_all = qx.to(torch.int16).abs().amax(dim=1)
+    assert int(q_all.min()) == 127 and int(q_all.max()) == 127
+    assert torch.isfinite(y.float()).all()
+
+
+def test_config_qkv_256_sampled_rows():
+    sampled_rows_case(synth.QKV_256)
+
+
+def test_config_fc1_gelu_512_sampled_rows():
+    sampled_rows_case(synth.FC1_512)
+
+
+@pytest.mark.parametrize("case", [synth.FC2_512_W8, synth.FC2_512_W4], ids=["w8", "w4"])
+def test_config_fc2_512_sampled_rows(case):
+    sampled_rows_case(case, rows_wanted=48)
+
+
+# ------------------------------------------------------------------ qc_latent_delta
+
+@pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 100003, 16 * 4 * 16 * 64 * 64, 9_000_001])
+def test_latent_delta_matches_oracle(n):
+    cur, prev = synth.latent_pair(seed=n % 97, n=n)
+    ref = oracle.latent_delta(cur, prev)
+    ws = qc.latent_delta_workspace_t(n)
+    out = qc.latent_delta_t(dev(cur), dev(prev), workspace=ws).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(out - ref) <= 1e-5 * np.abs(ref)), (out, ref)
+    # same workspace again (control words must have been left zeroed), identical bits
+    out2 = qc.latent_delta_t(dev(cur), dev(prev), workspace=ws).cpu().numpy()
+    assert bits_equal(out2, out.astype(np.float32))
+
+
+def test_latent_delta_closed_forms_and_determinism():
+    n = 16 * 4 * 16 * 64 * 64
+    cur, prev = synth.latent_pair(n=n)
+    c, p = dev(cur), dev(prev)
+    ws = qc.latent_delta_workspace_t(n)
+    assert qc.latent_delta_t(p, p, workspace=ws).cpu().tolist()[0] == 0.0
+    half = qc.latent_delta_t(p * 0.5, p, workspace=ws).cpu().numpy()
+    assert abs(half[2] - 0.5) < 1e-6
+    z = torch.zeros_like(p)
+    assert qc.latent_delta_t(p, z, workspace=ws).cpu().tolist()[2] == math.inf
+    assert qc.latent_delta_t(z, z, workspace=ws).cpu().tolist() == [0.0, 0.0, 0.0]
+    first = qc.latent_delta_t(c, p, workspace=ws).cpu().numpy()
+    assert 0.009 < first[2] < 0.011
+    for _ in range(10):
+        assert bits_equal(qc.latent_delta_t(c, p, workspace=ws).cpu().numpy(), first)
