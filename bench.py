@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+A step is one pass of the per-step hot path over one batch of seeded synthetic input:
+qc_qlinear (per-token activation quantization + int8 MFMA GEMM + dequant/bias epilogue) on
+the STDiT QKV projection of a 256x256 video (X bf16 [16384, 1152], W int8 [3456, 1152],
+bf16 out) followed by qc_latent_delta on two [16, 4, 16, 64, 64] float latents.  The weight
+is packed once before the timed region (it is an offline step of the method); its time is
+reported beside the result.  Inputs are resident in HBM when timing starts.
+
+Prints ONE JSON line.  `value` = 2*M*N*K integer ops of the step divided by the step time.
+`roofline` describes the dominant kernel (the GEMM), timed with HIP events in a second pass
+over the same launches; `kernels` adds the HBM-bound kernels; `cpu_baseline` is the CPU
+oracle timed on this host's cores on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, 5.0 POP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
+
+# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this
+# script (profiles/), scaled by the same counters on a plain copy; None = not collected yet.
+MEASURED_TRAFFIC_BYTES = {"gemm": None, "quant": None, "delta": None}
+
+
+def event_times_us(fn, iters):
+    """Per-launch durations of fn() measured with HIP events on the current stream."""
+    import torch
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        starts[i].record()
+        fn()
+        stops[i].record()
+    torch.cuda.synchronize()
+    return [starts[i].elapsed_time(stops[i]) * 1e3 for i in range(iters)]
+
+
+def cpu_baseline(case, target_seconds=15.0):
+    """The oracle as it stands on a bounded sample of token rows (all N, all K)."""
+    import numpy as np
+    import oracle
+    W, b = case.weight(), case.bias()
+    qw, sw = oracle.quant_weight(W, case.bits)
+    threads = oracle.num_threads()
+    probe_rows = 64
+    x = case.x_rows(0, probe_rows)
+    t0 = time.perf_counter()
+    oracle.qlinear(x, qw, sw, b)
+    per_row = (time.perf_counter() - t0) / probe_rows
+    rows = int(min(case.M, max(probe_rows, target_seconds / per_row)))
+    rows -= rows % 64
+    x = case.x_rows(0, rows)
+    t0 = time.perf_counter()
+    oracle.qlinear(x, qw, sw, b)
+    dt = time.perf_counter() - t0
+    tops = 2.0 * rows * case.N * case.K / dt / 1e12
+    return {"value": tops, "unit": "TOPS", "cores": threads, "kind": "oracle",
+            "sample": f"first {rows} of {case.M} token rows x all N={case.N} x K={case.K} "
+                      f"(quantize + int32 GEMM + epilogue), {dt:.2f} s, OpenMP over rows",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by token "
+              "rows without any exchange, see DESIGN.md", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2503_06545_amd import binding as qc
+    from paper_2503_06545_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qc.lib()  # fail loudly if libqc.so is missing
+
+    case = synth.QKV_256
+    M, K, N = case.M, case.K, case.N
+    x = torch.from_numpy(case.x().view(np.int16)).cuda().view(torch.bfloat16)
+    W = torch.from_numpy(case.weight()).cuda()
+    bias = torch.from_numpy(case.bias()).cuda()
+    cur_h, prev_h = synth.latent_pair(seed=0)
+    cur, prev = torch.from_numpy(cur_h).cuda(), torch.from_numpy(prev_h).cuda()
+    n_lat = cur.numel()
+
+    pw = qc.pack_weight_t(W, case.bits)
+    ws = qc.qlinear_workspace_t(M, K, N)
+    dws = qc.latent_delta_workspace_t(n_lat)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    out3 = torch.empty(3, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    epi = qc.EPI[case.epi]
+
+    def check(st):
+        if st != qc.QC_OK:
+            raise qc.QcError(st, "bench step")
+
+    def step():
+        check(qc.qc_qlinear(x.data_ptr(), qc.QC_BF16, M, K, pw.blob.data_ptr(), pw.scale.data_ptr(),
+                            case.bits, N, bias.data_ptr(), epi, Y.data_ptr(), qc.QC_OUT_BF16,
+                            ws.data_ptr(), ws.numel(), stream))
+        check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
+                                 dws.data_ptr(), dws.numel(), stream))
+
+    def quant_stage():
+        check(qc.qc_qlinear_quant(x.data_ptr(), qc.QC_BF16, M, K, ws.data_ptr(), ws.numel(), stream))
+
+    def gemm_stage():
+        check(qc.qc_qlinear_gemm(ws.data_ptr(), ws.numel(), M, K, pw.blob.data_ptr(),
+                                 pw.scale.data_ptr(), case.bits, N, bias.data_ptr(), epi,
+                                 Y.data_ptr(), qc.QC_OUT_BF16, stream))
+
+    def delta_stage():
+        check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
+                                 dws.data_ptr(), dws.numel(), stream))
+
+    def pack_stage():
+        check(qc.qc_pack_weight(W.data_ptr(), N, K, case.bits, pw.blob.data_ptr(),
+                                pw.scale.data_ptr(), stream))
+
+    # ---- headline: K steps between two full synchronisations ----------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ops = 2.0 * M * N * K
+    value = ops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations: the same launches again, each bracketed by HIP events ----
+    iters = max(20, min(args.steps, 200))
+    per = {}
+    for name, fn in (("quant", quant_stage), ("gemm", gemm_stage), ("delta", delta_stage),
+                     ("pack", pack_stage)):
+        for _ in range(5):
+            fn()
+        t = event_times_us(fn, iters)
+        per[name] = {"avg_us": sum(t) / len(t), "min_us": min(t)}
+
+    gemm_us = per["gemm"]["avg_us"]
+    gemm_tops = ops / (gemm_us * 1e-6) / 1e12
+    quant_bytes = M * K * 2 + M * K + 4 * M
+    delta_bytes = 2 * n_lat * 4 + 12
+    quant_gbs = quant_bytes / (per["quant"]["avg_us"] * 1e-6) / 1e9
+    delta_gbs = delta_bytes / (per["delta"]["avg_us"] * 1e-6) / 1e9
+
+    result = {
+        "metric": "quantized-linear int8 TOPS, whole qc_qlinear + qc_latent_delta step, 1 MI355X",
+        "value": round(value, 2),
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 (int32 accumulate; bf16 in/out, fp32 scales)",
+        "data": "synthetic",
+        "config": {"workload": "STDiT QKV projection 256x256 (BASELINE configs[1]): X bf16 "
+                               "[16384,1152] N(0,1) with 12 outlier columns x20, W8A8 [3456,1152], "
+                               "bias, bf16 out; + latent delta on 2 x [16,4,16,64,64] fp32",
+                   "M": M, "K": K, "N": N, "weight_bits": case.bits, "seed": case.seed,
+                   "offline_not_in_step": "qc_pack_weight"},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<8, bf16, none>",
+                     "achieved": round(gemm_tops, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES["gemm"],
+                     "ops_per_launch": ops, "avg_launch_us": round(gemm_us, 2)},
+        "kernels": {
+            "quant_act": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": PEAK_HBM_GBS,
+                          "unit": "GB/s", "frac": round(quant_gbs / PEAK_HBM_GBS, 4),
+                          "bytes_per_launch": quant_bytes, "avg_launch_us": round(per["quant"]["avg_us"], 2),
+                          "traffic": MEASURED_TRAFFIC_BYTES["quant"]},
+            "latent_delta": {"bound": "hbm", "achieved": round(delta_gbs, 1), "peak": PEAK_HBM_GBS,
+                             "unit": "GB/s", "frac": round(delta_gbs / PEAK_HBM_GBS, 4),
+                             "bytes_per_launch": delta_bytes, "avg_launch_us": round(per["delta"]["avg_us"], 2),
+                             "note": "33.5 MB of inputs stay resident in the 256 MB Infinity Cache between launches (warm)",
+                             "traffic": MEASURED_TRAFFIC_BYTES["delta"]},
+            "pack_weight_offline": {"avg_launch_us": round(per["pack"]["avg_us"], 2)},
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -124,6 +124,19 @@ qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K, const vo
                      qc_epilogue epi, void *Y, qc_out ydt, void *workspace,
                      size_t workspace_bytes, void *stream);
 
+/* The two halves of qc_qlinear as calls of their own: qc_qlinear(..) is exactly
+ * qc_qlinear_quant(..) followed by qc_qlinear_gemm(..) on the same stream.  They serve a
+ * caller that feeds one activation tensor to several linears (quantize once, multiply
+ * several times) and the benchmark, which times the halves separately.
+ *   qc_qlinear_quant  X [M, K] -> workspace (codes in the GEMM's tiled order + scales)
+ *   qc_qlinear_gemm   workspace written by qc_qlinear_quant for the same M, K -> Y [M, N]
+ * Arguments, sizes and errors as for qc_qlinear. */
+qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K, void *workspace,
+                           size_t workspace_bytes, void *stream);
+qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t M, int64_t K,
+                          const void *packed, const float *w_scale, int bits, int64_t N,
+                          const float *bias, qc_epilogue epi, void *Y, qc_out ydt, void *stream);
+
 /* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
  * activation codes and scales it used out of the workspace in canonical order:
  * qx int8 [M, K] row major, x_scale float [M]. */

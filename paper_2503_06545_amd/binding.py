@@ -22,7 +22,7 @@ QC_MAX_K = 131072
 EXPORTS = (
     "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",
     "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
-    "qc_qlinear", "qc_debug_workspace_act", "qc_latent_delta", "qc_latent_delta_workspace_init",
+    "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_debug_workspace_act", "qc_latent_delta", "qc_latent_delta_workspace_init",
 )
 
 
@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.qc_quant_act.argtypes = [vp, i32, i64, i64, vp, vp, vp]
         L.qc_qlinear.restype = i32
         L.qc_qlinear.argtypes = [vp, i32, i64, i64, vp, vp, i32, i64, vp, i32, vp, i32, vp, sz, vp]
+        L.qc_qlinear_quant.restype = i32
+        L.qc_qlinear_quant.argtypes = [vp, i32, i64, i64, vp, sz, vp]
+        L.qc_qlinear_gemm.restype = i32
+        L.qc_qlinear_gemm.argtypes = [vp, sz, i64, i64, vp, vp, i32, i64, vp, i32, vp, i32, vp]
         L.qc_debug_workspace_act.restype = i32
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
@@ -109,6 +113,16 @@ def qc_qlinear(X, xdt, M, K, packed, w_scale, bits, N, bias, epi, Y, ydt, worksp
                workspace_bytes, stream=0) -> int:
     return int(lib().qc_qlinear(X, xdt, M, K, packed, w_scale, bits, N, bias, epi, Y, ydt,
                                 workspace, workspace_bytes, stream))
+
+
+def qc_qlinear_quant(X, xdt, M, K, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_quant(X, xdt, M, K, workspace, workspace_bytes, stream))
+
+
+def qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                    stream=0) -> int:
+    return int(lib().qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N,
+                                     bias, epi, Y, ydt, stream))
 
 
 def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:

@@ -36,10 +36,47 @@ extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }
 
+extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                      void *workspace, size_t workspace_bytes, void *stream) {
+    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    uint8_t *base = (uint8_t *)workspace;
+    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
+                                    (float *)base, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
+                                     int64_t K, const void *packed, const float *w_scale, int bits,
+                                     int64_t N, const float *bias, qc_epilogue epi, void *Y,
+                                     qc_out ydt, void *stream) {
+    if (!packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
+        return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
+        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    const int64_t tiles = (ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN);
+    if (tiles > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    const uint8_t *base = (const uint8_t *)workspace;
+    hipError_t e = launch_gemm(base + ws.scale_bytes, (const float *)base, (const uint8_t *)packed,
+                               w_scale, bias, Y, M, N, K, bits, epi, ydt, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
 extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                 const void *packed, const float *w_scale, int bits, int64_t N,
                                 const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                                 void *workspace, size_t workspace_bytes, void *stream) {
+    // every argument is checked before the first launch, so a failed call has no side effect
     if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
         return QC_ERR_INVALID_ARG;
     if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
@@ -49,18 +86,12 @@ extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t 
         !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
         return QC_ERR_INVALID_ARG;
     if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     const ActWorkspace ws = act_workspace(M, K);
-    const int64_t tiles = (ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN);
-    if (tiles > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-
-    uint8_t *base = (uint8_t *)workspace;
-    float *x_scale = (float *)base;
-    uint8_t *x_tiled = base + ws.scale_bytes;
-    hipStream_t s = (hipStream_t)stream;
-    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, x_tiled, ws.KF, x_scale, s);
-    if (e != hipSuccess) return QC_ERR_DEVICE;
-    e = launch_gemm(x_tiled, x_scale, (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
-                    ydt, s);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    qc_status st = qc_qlinear_quant(X, xdt, M, K, workspace, workspace_bytes, stream);
+    if (st != QC_OK) return st;
+    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
+                           ydt, stream);
 }

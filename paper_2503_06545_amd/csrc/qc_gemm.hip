@@ -4,14 +4,20 @@
 //   acc[m, n] = sum_k qx[m, k] * qw[n, k]          exact, int32, v_mfma_i32_32x32x32_i8
 //   Y[m, n]   = act(acc * sx[m] * sw[n] + bias[n])
 //
-// Block tile 256 tokens x 128 channels, 4 wavefronts as 2 (tokens) x 2 (channels), each
-// 128 x 64 = 4 x 2 MFMA tiles (128 accumulator registers), two blocks per CU so that one
+// Block tile 256 tokens x 128 channels, 4 wavefronts stacked along the tokens, each
+// 64 x 128 = 2 x 4 MFMA tiles (128 accumulator registers), two blocks per CU so that one
 // block's epilogue overlaps the other's MFMA loop.  Operands arrive pre-arranged as 1 KiB
-// MFMA fragments (see qc_internal.h), so HBM -> LDS is a linear direct-to-LDS copy and
-// LDS -> register reads are linear 16 B/lane and conflict free.  K advances 64 per stage
-// through a 3-deep ring of LDS buffers.  The weight is the MFMA "A" operand (rows of the
-// result tile = channels) and the tokens the "B" operand, so a lane owns one token and runs
-// of consecutive channels, which the weight row permutation widens to 8.
+// MFMA fragments (see qc_internal.h).  The weight tile, which all four wavefronts use, goes
+// HBM -> LDS by linear direct-to-LDS copies through a 3-deep ring of 64-k stages and is read
+// back 16 B/lane, conflict free; the activation fragments are private to a wavefront and go
+// HBM -> registers directly (LDS writes are the scarce resource: about 64 B/clk/CU against
+// 256 B/clk/CU for reads).  Inside a stage the weight reads of the next 32 k are in flight
+// under the MFMAs of the current 32 k.  Tokens are the MFMA "A" operand (rows of the result
+// tile) and channels the "B" operand (columns = lanes); the weight row permutation makes a
+// lane's four tiles four consecutive channels, so half a wavefront stores 128 consecutive
+// channels of one token at a time.
+#include <type_traits>
+
 #include "qc_internal.h"
 
 namespace qc {
@@ -19,25 +25,27 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
-constexpr int kStages = 3;
-constexpr int kXFrags = (kTileM / kFragRows) * 2;  // 16 fragments of X per 64-k stage
+constexpr int kStages = 3;   // LDS ring of weight stages
+constexpr int kXSlots = 3;   // register ring of activation stages
 
 template <int BITS>
 struct StageLayout {
-    // fragments (1 KiB each) of W per stage: 8-bit 4 row blocks x 2 k fragments; 4-bit one
-    // 64-k unit per row block
+    // Only the weight tile goes through LDS (all four wavefronts use all of it).  Fragments
+    // (1 KiB each) per 64-k stage: 8 bit 4 channel blocks x 2 k fragments; 4 bit one 64-k
+    // nibble unit per channel block.
     static constexpr int kWFrags = BITS == 8 ? (kTileN / kFragRows) * 2 : (kTileN / kFragRows);
-    static constexpr int kFrags = kWFrags + kXFrags;
-    static constexpr int kBytes = kFrags * kFragBytes;
-    static constexpr int kFragsPerWave = kFrags / 4;
-    static_assert(kFrags % 4 == 0, "fragments must split evenly over 4 wavefronts");
+    static constexpr int kBytes = kWFrags * kFragBytes;
+    static constexpr int kFragsPerWave = kWFrags / 4;
+    static_assert(kWFrags % 4 == 0, "fragments must split evenly over 4 wavefronts");
 };
 
 struct GemmArgs {
     const uint8_t *x_tiled;
-    const float *x_scale;
+    const float *x_scale;   // Mp entries (padded), 16 B aligned
     const uint8_t *w_codes;
     const float *w_scale;
     const float *bias;
@@ -63,12 +71,10 @@ __device__ inline float gelu_tanh_f(float y) {
 
 __device__ inline float gelu_erf_f(float y) { return 0.5f * y * (1.0f + erff(y * 0.70710678118654752f)); }
 
+// two floats -> two bf16 (round to nearest even), one v_cvt_pk_bf16_f32
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-    // round to nearest even on the dropped 16 bits
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    const f2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf2));
 }
 
 // Map the launch's block index to a tile so that the blocks resident on one XCD at a time
@@ -87,192 +93,271 @@ __device__ inline void tile_of_block(int b, int nblocks, int m_tiles, int n_tile
     nt = r / gm;
 }
 
+// vmcnt(n) with the other counters left unconstrained (gfx9 encoding, n < 16)
+#define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+#define QC_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+
 template <int BITS, int OUT, int EPI>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     using L = StageLayout<BITS>;
+    constexpr int FPW = L::kFragsPerWave;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wn = wave & 1, wm = wave >> 1;
     int mt, nt;
     tile_of_block(blockIdx.x, gridDim.x, a.m_tiles, a.n_tiles, mt, nt);
 
     const int stages = a.KF / 2;
-    // global source of each fragment this wavefront copies, at stage 0
-    const uint8_t *src[L::kFragsPerWave];
-    int src_step[L::kFragsPerWave];
+    // Weight fragments this wavefront copies HBM -> LDS, at stage 0.
+    const uint8_t *wsrc[FPW];
 #pragma unroll
-    for (int j = 0; j < L::kFragsPerWave; ++j) {
-        const int f = wave * L::kFragsPerWave + j;
-        if (f < L::kWFrags) {
-            if (BITS == 8) {
-                const int rb = f >> 1, kf = f & 1;
-                src[j] = a.w_codes + ((int64_t)(nt * 4 + rb) * a.KF + kf) * kFragBytes;
-                src_step[j] = 2 * kFragBytes;
-            } else {
-                src[j] = a.w_codes + ((int64_t)(nt * 4 + f) * (a.KF / 2)) * kFragBytes;
-                src_step[j] = kFragBytes;
-            }
+    for (int j = 0; j < FPW; ++j) {
+        const int f = wave * FPW + j;
+        if (BITS == 8) {
+            const int rb = f >> 1, kf = f & 1;
+            wsrc[j] = a.w_codes + ((int64_t)(nt * 4 + rb) * a.KF + kf) * kFragBytes + lane * 16;
         } else {
-            const int fx = f - L::kWFrags;
-            const int rb = fx >> 1, kf = fx & 1;
-            src[j] = a.x_tiled + ((int64_t)(mt * 8 + rb) * a.KF + kf) * kFragBytes;
-            src_step[j] = 2 * kFragBytes;
+            wsrc[j] = a.w_codes + ((int64_t)(nt * 4 + f) * (a.KF / 2)) * kFragBytes + lane * 16;
         }
-        src[j] += lane * 16;
     }
-
-    auto issue = [&](int stage) {
-        uint8_t *buf = lds + (stage % kStages) * L::kBytes;
+    constexpr int kWStep = BITS == 8 ? 2 * kFragBytes : kFragBytes;
+    // copy the weight fragments of K stage `stage` into ring buffer `ring % 3`
+    auto issue_w = [&](int stage, int ring) {
+        uint8_t *buf = lds + (ring % kStages) * L::kBytes;
 #pragma unroll
-        for (int j = 0; j < L::kFragsPerWave; ++j) {
-            const int f = wave * L::kFragsPerWave + j;
-            lds_dma_16(src[j] + (int64_t)stage * src_step[j], buf + f * kFragBytes);
-        }
+        for (int j = 0; j < FPW; ++j)
+            lds_dma_16(wsrc[j] + (int64_t)stage * kWStep, buf + (wave * FPW + j) * kFragBytes);
     };
+
+    // Activation fragments are private to a wavefront (its 64 tokens), so they skip LDS:
+    // HBM -> registers, 16 B per lane, two stages ahead.  xq[slot][i][kf]: tokens 32 i ..,
+    // k half kf of the stage held in `slot`.  Loads and LDS reads are asm so that they stay
+    // in flight across loop iterations under explicit s_waitcnt counts; each wait names the
+    // registers it makes valid, which orders the MFMAs that consume them behind it.
+    v4i xq[kXSlots][2][2];
+    const uint8_t *xsrc0 = a.x_tiled + ((int64_t)(mt * 8 + wave * 2 + 0) * a.KF) * kFragBytes + lane * 16;
+    const uint8_t *xsrc1 = a.x_tiled + ((int64_t)(mt * 8 + wave * 2 + 1) * a.KF) * kFragBytes + lane * 16;
+
+#define QC_GLOBAL_LOAD(dst, ptr, imm) \
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(ptr), "n"(imm) : "memory")
+#define QC_ISSUE_X(stage, SLOT)                                              \
+    do {                                                                     \
+        const uint8_t *p0_ = xsrc0 + (int64_t)(stage) * (2 * kFragBytes);    \
+        const uint8_t *p1_ = xsrc1 + (int64_t)(stage) * (2 * kFragBytes);    \
+        QC_GLOBAL_LOAD(xq[SLOT][0][0], p0_, 0);                              \
+        QC_GLOBAL_LOAD(xq[SLOT][0][1], p0_, kFragBytes);                     \
+        QC_GLOBAL_LOAD(xq[SLOT][1][0], p1_, 0);                              \
+        QC_GLOBAL_LOAD(xq[SLOT][1][1], p1_, kFragBytes);                     \
+    } while (0)
+#define QC_WAIT_X(n, SLOT)                                                                    \
+    asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(xq[SLOT][0][0]), "+v"(xq[SLOT][0][1]),      \
+                 "+v"(xq[SLOT][1][0]), "+v"(xq[SLOT][1][1]))
+
+    // LDS -> registers for the weight fragments.
+    //   wr[kf][t]: t-th 32-channel block (8 bit);  wr[0][t]: its 64-k nibble unit (4 bit)
+    v4i wr[2][4];
+    const uint32_t lds_lane = (uint32_t)(uintptr_t)lds + lane * 16;  // LDS byte address of this lane
+#define QC_DS_READ(dst, addr, imm) \
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
+#define QC_READ_W(stage, KF)                                                         \
+    do {                                                                             \
+        const uint32_t base_ = lds_lane + ((stage) % kStages) * L::kBytes;           \
+        if (BITS == 8) {                                                             \
+            QC_DS_READ(wr[KF][0], base_, (0 * 2 + KF) * kFragBytes);                 \
+            QC_DS_READ(wr[KF][1], base_, (1 * 2 + KF) * kFragBytes);                 \
+            QC_DS_READ(wr[KF][2], base_, (2 * 2 + KF) * kFragBytes);                 \
+            QC_DS_READ(wr[KF][3], base_, (3 * 2 + KF) * kFragBytes);                 \
+        } else if (KF == 0) {                                                        \
+            QC_DS_READ(wr[0][0], base_, 0 * kFragBytes);                             \
+            QC_DS_READ(wr[0][1], base_, 1 * kFragBytes);                             \
+            QC_DS_READ(wr[0][2], base_, 2 * kFragBytes);                             \
+            QC_DS_READ(wr[0][3], base_, 3 * kFragBytes);                             \
+        }                                                                            \
+    } while (0)
+#define QC_WAIT_W(n, KF) \
+    asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(wr[KF][0]), "+v"(wr[KF][1]), "+v"(wr[KF][2]), "+v"(wr[KF][3]))
 
     v16i acc[2][4];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][j][r] = 0;
+            for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
 
-    issue(0);
-    if (stages > 1) issue(1);
-
-    for (int s = 0; s < stages; ++s) {
-        if (s + 1 < stages) __builtin_amdgcn_s_waitcnt(0x0F70 | L::kFragsPerWave);  // vmcnt <= one stage
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                                     // vmcnt == 0
-        __builtin_amdgcn_s_barrier();
-        if (s + 2 < stages) issue(s + 2);
-
-        const uint8_t *buf = lds + (s % kStages) * L::kBytes;
-        const uint8_t *xb = buf + L::kWFrags * kFragBytes + lane * 16;
-        if (BITS == 8) {
+    // 4 bit: nibbles -> int8 operand dwords holding 16 * code
+    auto unpack = [&](v4i (&w)[4], int kf) {
 #pragma unroll
-            for (int kf = 0; kf < 2; ++kf) {
-                v4i wa[2], xbv[4];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-                    wa[t] = *reinterpret_cast<const v4i *>(buf + ((wn * 2 + t) * 2 + kf) * kFragBytes + lane * 16);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    xbv[j] = *reinterpret_cast<const v4i *>(xb + ((wm * 4 + j) * 2 + kf) * kFragBytes);
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[t][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[t], xbv[j], acc[t][j], 0, 0, 0);
-            }
-        } else {
-            v4i packed[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-                packed[t] = *reinterpret_cast<const v4i *>(buf + (wn * 2 + t) * kFragBytes + lane * 16);
-#pragma unroll
-            for (int kf = 0; kf < 2; ++kf) {
-                v4i wa[2], xbv[4];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const uint32_t v0 = (uint32_t)packed[t][2 * kf], v1 = (uint32_t)packed[t][2 * kf + 1];
-                    wa[t][0] = (int)((v0 << 4) & 0xF0F0F0F0u);
-                    wa[t][1] = (int)(v0 & 0xF0F0F0F0u);
-                    wa[t][2] = (int)((v1 << 4) & 0xF0F0F0F0u);
-                    wa[t][3] = (int)(v1 & 0xF0F0F0F0u);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    xbv[j] = *reinterpret_cast<const v4i *>(xb + ((wm * 4 + j) * 2 + kf) * kFragBytes);
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[t][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wa[t], xbv[j], acc[t][j], 0, 0, 0);
-            }
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t v0 = (uint32_t)wr[0][t][2 * kf], v1 = (uint32_t)wr[0][t][2 * kf + 1];
+            w[t][0] = (int)((v0 << 4) & 0xF0F0F0F0u);
+            w[t][1] = (int)(v0 & 0xF0F0F0F0u);
+            w[t][2] = (int)((v1 << 4) & 0xF0F0F0F0u);
+            w[t][3] = (int)(v1 & 0xF0F0F0F0u);
         }
+    };
+
+    // One 64-k stage.  SLOT = stage % 3 and NEXT2 = (stage + 2) % 3 are literal constants (the
+    // loop is unrolled by three) so the activation ring stays in fixed registers.
+    // VMEM operations complete in issue order; the issue order per wavefront is
+    //   W(0) X(0) W(1) X(1) W(2), then in stage s: X(s+2), W(s+3)
+    // so behind X(s) come W(s+1) X(s+1) W(s+2) X(s+2) (2 FPW + 8 operations) and behind
+    // W(s+1) come X(s+1) W(s+2) X(s+2) (FPW + 8).  Past the end of K the stage index is
+    // clamped to the last stage: those copies repeat data that is not used again (they hit
+    // in cache), which keeps the instruction stream and the wait counts uniform.
+    const int last = stages - 1;
+#define QC_CLAMP(st) ((st) < last ? (st) : last)
+#define QC_STAGE(s, SLOT, NEXT2)                                                               \
+    do {                                                                                       \
+        QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
+        QC_READ_W((s), 1);                                                                     \
+        if (BITS == 8) QC_WAIT_W(4, 0); else QC_WAIT_W(0, 0);   /* k half 0 of W(s) is here */ \
+        if (BITS == 8) QC_WAIT_X(12, SLOT); else QC_WAIT_X(10, SLOT);      /* X(s) is here */  \
+        v4i w4a[4], w4b[4];                                                                    \
+        if (BITS == 4) { unpack(w4a, 0); unpack(w4b, 1); }                                     \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                          \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                      \
+                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
+                    xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        QC_WAIT_VMCNT(FPW + 8);                                         /* W(s+1) has landed */\
+        /* this wavefront's reads of W(s) are done ... */                                      \
+        if (BITS == 8) QC_WAIT_W(0, 1);                                                        \
+        __builtin_amdgcn_s_barrier(); /* ... and everybody else's: ring buffer s % 3 is free */\
+        asm volatile("" ::: "memory");                                                         \
+        issue_w(QC_CLAMP((s) + 3), (s) + 3);                                                   \
+        /* after the last stage this reads data that is not used */                            \
+        QC_READ_W((s) + 1, 0);                                                                 \
+        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                          \
+            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                      \
+                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
+                    xq[SLOT][i][1], BITS == 8 ? wr[1][t] : w4b[t], acc[i][t], 0, 0, 0);        \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+    } while (0)
+
+    // ---- main loop -------------------------------------------------------------------
+    issue_w(0, 0);
+    QC_ISSUE_X(0, 0);
+    issue_w(QC_CLAMP(1), 1);
+    QC_ISSUE_X(QC_CLAMP(1), 1);
+    issue_w(QC_CLAMP(2), 2);
+    QC_WAIT_VMCNT(8 + 2 * FPW);   // W(0) has landed: behind it are X(0) W(1) X(1) W(2)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    QC_READ_W(0, 0);
+
+    for (int s = 0; s < stages; s += 3) {
+        QC_STAGE(s, 0, 2);
+        QC_STAGE(s + 1, 1, 0);
+        QC_STAGE(s + 2, 2, 1);
     }
+    // drain everything still in flight before the registers are reused
+    QC_WAIT_W(0, 0);
+    QC_WAIT_X(0, 0);
+    QC_WAIT_X(0, 1);
+    QC_WAIT_X(0, 2);
+#undef QC_CLAMP
+#undef QC_STAGE
+#undef QC_WAIT_W
+#undef QC_READ_W
+#undef QC_DS_READ
+#undef QC_WAIT_X
+#undef QC_ISSUE_X
+#undef QC_GLOBAL_LOAD
 
     // ---- epilogue: registers -> Y --------------------------------------------------------
-    // Lane (c = lane % 32, h = lane / 32) of MFMA tile (t, j) holds, in register r, token
-    // m0 + 32 j + c and channel n0 + 16 (r / 4) + 8 h + 4 t + r % 4.
+    // Lane (c = lane % 32, h = lane / 32) of MFMA tile (i, t) holds, in register r, token
+    // m0 + 32 i + 8 (r / 4) + 4 h + r % 4 and channel n0 + 4 c + t.
     const int c = lane & 31, h = lane >> 5;
-    const int64_t m_base = (int64_t)mt * kTileM + wm * 128 + c;
-    const int64_t n_base = (int64_t)nt * kTileN + wn * 64 + 8 * h;
-    const bool vec_ok = (a.N % 8) == 0;
+    const int64_t n0 = (int64_t)nt * kTileN + 4 * c;
+    const int64_t m0 = (int64_t)mt * kTileM + wave * 64 + 4 * h;
+    if (n0 >= a.N) return;
+    const bool full = (a.N % 4) == 0 && n0 + 4 <= a.N;
 
-    float sx[4];
+    float sw[4], bs[4];
     if (OUT != QC_OUT_I32_ACC) {
+        if (full) {
+            const float4 s4 = *reinterpret_cast<const float4 *>(a.w_scale + n0);
+            sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
+            if (a.bias) {
+                const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + n0);
+                bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
+            } else {
+                bs[0] = bs[1] = bs[2] = bs[3] = 0.0f;
+            }
+        } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t m = m_base + 32 * j;
-            sx[j] = m < a.M ? a.x_scale[m] : 0.0f;
+            for (int t = 0; t < 4; ++t) {
+                const bool in = n0 + t < a.N;
+                sw[t] = in ? a.w_scale[n0 + t] : 0.0f;
+                bs[t] = (in && a.bias) ? a.bias[n0 + t] : 0.0f;
+            }
+        }
+        if (BITS == 4) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) sw[t] *= 0.0625f;  // operands carried codes times 16
         }
     }
 
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int64_t n0 = n_base + 16 * g;
-        if (n0 >= a.N) continue;
-        const bool full = vec_ok && n0 + 8 <= a.N;
-        float sw[8], bs[8];
-        if (OUT != QC_OUT_I32_ACC) {
+    for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool in = n0 + e < a.N;
-                sw[e] = in ? a.w_scale[n0 + e] : 0.0f;
-                if (BITS == 4) sw[e] *= 0.0625f;  // operands carried codes times 16
-                bs[e] = (in && a.bias) ? a.bias[n0 + e] : 0.0f;
+        for (int g = 0; g < 4; ++g) {
+            const int64_t m4 = m0 + 32 * i + 8 * g;
+            if (m4 >= a.M) continue;
+            float sx[4] = {0.f, 0.f, 0.f, 0.f};
+            if (OUT != QC_OUT_I32_ACC) {
+                const float4 x4 = *reinterpret_cast<const float4 *>(a.x_scale + m4);
+                sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
             }
-        }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t m = m_base + 32 * j;
-            if (m >= a.M) continue;
-            int raw[8];
+            for (int q = 0; q < 4; ++q) {
+                const int64_t m = m4 + q;
+                if (m >= a.M) continue;
+                int raw[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) raw[e] = acc[e >> 2][j][4 * g + (e & 3)];
-            if (OUT == QC_OUT_I32_ACC) {
-                int32_t *y = reinterpret_cast<int32_t *>(a.Y) + m * a.N + n0;
+                for (int t = 0; t < 4; ++t) raw[t] = acc[i][t][4 * g + q];
+                if (OUT == QC_OUT_I32_ACC) {
+                    int32_t *y = reinterpret_cast<int32_t *>(a.Y) + m * a.N + n0;
+                    if (BITS == 4) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) if (BITS == 4) raw[e] >>= 4;  // exact: multiples of 16
-                if (full) {
-                    reinterpret_cast<int4 *>(y)[0] = make_int4(raw[0], raw[1], raw[2], raw[3]);
-                    reinterpret_cast<int4 *>(y)[1] = make_int4(raw[4], raw[5], raw[6], raw[7]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) if (n0 + e < a.N) y[e] = raw[e];
-                }
-            } else {
-                float v[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    float y = fmaf((float)raw[e] * sx[j], sw[e], bs[e]);
-                    if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
-                    else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
-                    v[e] = y;
-                }
-                if (OUT == QC_OUT_F32) {
-                    float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
+                        for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
+                    }
                     if (full) {
-                        reinterpret_cast<float4 *>(y)[0] = make_float4(v[0], v[1], v[2], v[3]);
-                        reinterpret_cast<float4 *>(y)[1] = make_float4(v[4], v[5], v[6], v[7]);
+                        *reinterpret_cast<int4 *>(y) = make_int4(raw[0], raw[1], raw[2], raw[3]);
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) if (n0 + e < a.N) y[e] = v[e];
+                        for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
                     }
                 } else {
-                    uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
-                    if (full) {
-                        *reinterpret_cast<uint4 *>(y) =
-                            make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                       pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                    } else {
+                    float v[4];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (n0 + e < a.N) y[e] = (uint16_t)(pack_bf16x2(v[e], 0.0f) & 0xffffu);
+                    for (int t = 0; t < 4; ++t) {
+                        float y = fmaf((float)raw[t] * sx[q], sw[t], bs[t]);
+                        if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
+                        else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
+                        v[t] = y;
+                    }
+                    if (OUT == QC_OUT_F32) {
+                        float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
+                        if (full) {
+                            *reinterpret_cast<float4 *>(y) = make_float4(v[0], v[1], v[2], v[3]);
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
+                        }
+                    } else {
+                        uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
+                        const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
+                        if (full) {
+                            *reinterpret_cast<uint2 *>(y) = make_uint2(lo, hi);
+                        } else {
+                            if (n0 + 0 < a.N) y[0] = (uint16_t)(lo & 0xffffu);
+                            if (n0 + 1 < a.N) y[1] = (uint16_t)(lo >> 16);
+                            if (n0 + 2 < a.N) y[2] = (uint16_t)(hi & 0xffffu);
+                            if (n0 + 3 < a.N) y[3] = (uint16_t)(hi >> 16);
+                        }
                     }
                 }
             }

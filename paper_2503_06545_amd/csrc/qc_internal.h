@@ -15,13 +15,13 @@ namespace qc {
 // consecutive k of row l % 32, k half l / 32).  A fragment therefore covers 32 rows x 32 k,
 // and a wavefront moves it HBM -> LDS -> registers with fully linear 16 B/lane accesses.
 //
-//   fragment index   = (row / 32) * KF + k / 32          KF = Kp / 32, Kp = K rounded up to 64
+//   fragment index   = (row / 32) * KF + k / 32          KF = Kp / 32, Kp = K rounded up to 192
 //   byte in fragment = (((k % 32) / 16) * 32 + row % 32) * 16 + k % 16
 //
 // Activations use their token index as `row`.  Weights use a permuted row index p so that a
-// lane of the GEMM ends up holding 8 consecutive output channels (one 16 B bf16 store):
-// inside each group of 64 channels, channel n = 64 G + r sits at
-//   p = 64 G + 32 * ((r / 4) % 2) + 8 * (r / 16) + 4 * ((r / 8) % 2) + r % 4.
+// lane of the GEMM ends up holding 4 consecutive output channels of one token (one 8 B bf16
+// or 16 B float store, 32 lanes covering 128 consecutive channels): inside each group of
+// 128 channels, channel n = 128 G + r sits at p = 128 G + 32 * (r % 4) + r / 4.
 // 4-bit weights keep the same (p, k) -> lane mapping but one 1 KiB unit spans 64 k: lane l
 // holds 8 bytes of nibbles for the even 32-k fragment and 8 bytes for the odd one.  Inside a
 // dword of 8 nibbles, k offset e (0..7) sits in nibble (e < 4 ? 2 e : 2 (e - 4) + 1), so that
@@ -30,7 +30,7 @@ namespace qc {
 constexpr int kFragRows = 32;
 constexpr int kFragK = 32;
 constexpr int kFragBytes = 1024;
-constexpr int kKAlign = 64;        // K is padded to this (one pipeline stage of the GEMM)
+constexpr int kKAlign = 192;       // K is padded to this: three 64-k pipeline stages of the GEMM
 constexpr int kTileM = 256;        // GEMM block tile, tokens
 constexpr int kTileN = 128;        // GEMM block tile, output channels
 constexpr int kPackedHeaderBytes = 256;
@@ -45,8 +45,8 @@ __host__ __device__ inline int64_t frag_offset(int64_t row, int64_t k, int64_t K
 }
 
 __host__ __device__ inline int64_t weight_row_of_channel(int64_t n) {
-    int64_t r = n % 64;
-    return (n - r) + 32 * ((r / 4) % 2) + 8 * (r / 16) + 4 * ((r / 8) % 2) + r % 4;
+    const int64_t r = n % 128;
+    return (n - r) + 32 * (r % 4) + r / 4;
 }
 
 // workspace of qc_qlinear: [ x_scale: Mp floats ][ tiled codes: Mp * Kp bytes ]

@@ -33,16 +33,16 @@ def test_version_and_status_strings():
 
 
 def test_size_queries():
-    # int8: padded to 128 channels x 64 k, plus a 256-byte header
+    # int8: padded to 128 channels x 192 k, plus a 256-byte header
     assert qc.qc_packed_weight_bytes(3456, 1152, 8) == 256 + 3456 * 1152
     assert qc.qc_packed_weight_bytes(1152, 4608, 4) == 256 + 1152 * 4608 // 2
-    assert qc.qc_packed_weight_bytes(200, 100, 8) == 256 + 256 * 128
+    assert qc.qc_packed_weight_bytes(200, 100, 8) == 256 + 256 * 192
     assert qc.qc_packed_weight_bytes(10, 15, 4) == 0          # odd K with 4 bits
     assert qc.qc_packed_weight_bytes(10, 16, 5) == 0
     assert qc.qc_packed_weight_bytes(0, 16, 8) == 0
     assert qc.qc_packed_weight_bytes(10, qc.QC_MAX_K + 1, 8) == 0
     assert qc.qc_qlinear_workspace_bytes(16384, 1152, 3456) == 16384 * 4 + 16384 * 1152
-    assert qc.qc_qlinear_workspace_bytes(300, 100, 7) == 512 * 4 + 512 * 128
+    assert qc.qc_qlinear_workspace_bytes(300, 100, 7) == 512 * 4 + 512 * 192
     assert qc.qc_qlinear_workspace_bytes(0, 100, 7) == 0
     assert qc.qc_latent_delta_workspace_bytes(1 << 22) >= 256
     assert qc.qc_latent_delta_workspace_bytes(0) == 0
