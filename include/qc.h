@@ -149,19 +149,13 @@ qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K, in
  *   cur, prev  device, float [n]
  *   out3       device, float [3]: { sum|cur-prev|, sum|prev|, ratio }.
  *              ratio = +inf if the second sum is 0 and the first is not, 0 if both are.
- *   workspace  device, >= qc_latent_delta_workspace_bytes(n) bytes, 256-byte aligned.
- *              Its first 256 bytes must be zero before the first call that uses it
- *              (qc_latent_delta_workspace_init does that); every call leaves them zero
- *              again, so one buffer serves any number of calls on one stream.  Two
- *              calls that overlap in time need two buffers.
+ *   workspace  device, >= qc_latent_delta_workspace_bytes(n) bytes, 256-byte aligned;
+ *              contents on entry are irrelevant (per-block partial sums).  Two calls that
+ *              overlap in time need two buffers.
  * The result is deterministic: the same inputs give the same bits on every run.
  * Errors: INVALID_ARG, WORKSPACE, DEVICE. */
 qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float *out3,
                           void *workspace, size_t workspace_bytes, void *stream);
-
-/* Zero the control words of a latent-delta workspace (a small fill kernel, safe
- * under stream capture). */
-qc_status qc_latent_delta_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

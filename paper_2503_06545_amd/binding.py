@@ -22,7 +22,7 @@ QC_MAX_K = 131072
 EXPORTS = (
     "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",
     "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
-    "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_debug_workspace_act", "qc_latent_delta", "qc_latent_delta_workspace_init",
+    "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_debug_workspace_act", "qc_latent_delta",
 )
 
 
@@ -69,8 +69,6 @@ def lib() -> ctypes.CDLL:
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
-        L.qc_latent_delta_workspace_init.restype = i32
-        L.qc_latent_delta_workspace_init.argtypes = [vp, sz, vp]
         _lib = L
     return _lib
 
@@ -131,10 +129,6 @@ def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
 
 def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) -> int:
     return int(lib().qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream))
-
-
-def qc_latent_delta_workspace_init(workspace, workspace_bytes, stream=0) -> int:
-    return int(lib().qc_latent_delta_workspace_init(workspace, workspace_bytes, stream))
 
 
 # ---- tensor helpers: allocate outputs with torch, pass addresses and the current stream ----
@@ -239,12 +233,8 @@ def debug_workspace_act_t(workspace, M: int, K: int):
 
 
 def latent_delta_workspace_t(n: int, device="cuda"):
-    """Workspace with its control words zeroed by the library's own fill kernel."""
     torch = _torch()
-    ws = torch.empty(qc_latent_delta_workspace_bytes(n), dtype=torch.uint8, device=device)
-    _check(qc_latent_delta_workspace_init(ws.data_ptr(), ws.numel(), _stream()),
-           "qc_latent_delta_workspace_init")
-    return ws
+    return torch.empty(qc_latent_delta_workspace_bytes(n), dtype=torch.uint8, device=device)
 
 
 def latent_delta_t(cur, prev, workspace=None, out3=None):

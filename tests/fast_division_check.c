@@ -1,0 +1,72 @@
+/*
+ * Host-side check of the division-free quotient the activation-quantization kernel uses:
+ *     r = RN(1 / s);  q = x * r;  q = fma(fma(-s, q, x), r, q)  (twice)
+ * against true IEEE binary32 division, over every bf16 input for many scales and over random
+ * binary32 inputs including constructed near-ties.  The arithmetic is retyped here on purpose
+ * (it shares no code with the GPU kernel): this validates the algorithm, the GPU parity
+ * tests validate the implementation.  Prints "pairs quotient_mismatches_that_matter
+ * code_mismatches"; quotient mismatches are only tolerated below 2^-30, where every code is 0.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+static float fast_quotient(float x, float s, float r) {
+    float q = x * r;
+    q = fmaf(fmaf(-s, q, x), r, q);
+    q = fmaf(fmaf(-s, q, x), r, q);
+    return q;
+}
+static float code_of(float q) { return fminf(fmaxf(rintf(q), -127.f), 127.f); }
+
+static uint64_t state = 88172645463325252ULL;
+static uint64_t next(void) { state ^= state << 13; state ^= state >> 7; state ^= state << 17; return state; }
+
+int main(int argc, char **argv) {
+    long scales = argc > 1 ? atol(argv[1]) : 400, randoms = argc > 2 ? atol(argv[2]) : 20000000;
+    long pairs = 0, bad_q = 0, bad_code = 0;
+    for (long si = 0; si < scales; ++si) {
+        uint32_t ab = (uint32_t)(next() & 0x7fffffff);
+        float a;
+        memcpy(&a, &ab, 4);
+        if (!(a > 0x1p-60f && a < 0x1p100f)) continue;
+        if (si % 2) { ab &= 0xffff0000u; memcpy(&a, &ab, 4); }
+        float s = a / 127.0f, r = 1.0f / s;
+        for (uint32_t hb = 0; hb < 65536; ++hb) {
+            uint32_t u = hb << 16;
+            float x;
+            memcpy(&x, &u, 4);
+            if (!(fabsf(x) <= a)) continue;
+            float q = x / s, f = fast_quotient(x, s, r);
+            ++pairs;
+            if (memcmp(&q, &f, 4) != 0 && fabsf(q) > 0x1p-30f) ++bad_q;
+            if (code_of(q) != code_of(f)) ++bad_code;
+        }
+    }
+    for (long it = 0; it < randoms; ++it) {
+        uint32_t ab = (uint32_t)(next() & 0x7fffffff);
+        float a, x;
+        memcpy(&a, &ab, 4);
+        if (!(a > 0x1p-60f && a < 0x1p100f)) continue;
+        float s = a / 127.0f, r = 1.0f / s;
+        if (it & 1) {
+            x = a * ((float)(next() & 0xffffff) / 8388608.0f - 1.0f);
+        } else { /* a half-integer multiple of s, nudged by a few ulps */
+            float k = (float)((int)(next() % 255) - 127) + 0.5f;
+            uint32_t xb;
+            x = k * s;
+            memcpy(&xb, &x, 4);
+            xb += (uint32_t)(next() % 5) - 2;
+            memcpy(&x, &xb, 4);
+        }
+        if (!(fabsf(x) <= a)) continue;
+        float q = x / s, f = fast_quotient(x, s, r);
+        ++pairs;
+        if (memcmp(&q, &f, 4) != 0 && fabsf(q) > 0x1p-30f) ++bad_q;
+        if (code_of(q) != code_of(f)) ++bad_code;
+    }
+    printf("%ld %ld %ld\n", pairs, bad_q, bad_code);
+    return 0;
+}

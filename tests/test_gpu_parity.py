@@ -277,7 +277,7 @@ def test_latent_delta_matches_oracle(n):
     ws = qc.latent_delta_workspace_t(n)
     out = qc.latent_delta_t(dev(cur), dev(prev), workspace=ws).cpu().numpy().astype(np.float64)
     assert np.all(np.abs(out - ref) <= 1e-5 * np.abs(ref)), (out, ref)
-    # same workspace again (control words must have been left zeroed), identical bits
+    # same workspace again, identical bits
     out2 = qc.latent_delta_t(dev(cur), dev(prev), workspace=ws).cpu().numpy()
     assert bits_equal(out2, out.astype(np.float32))
 
