@@ -73,8 +73,10 @@ def cpu_baseline(case, target_seconds=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=3000)
+    # the GPU needs some tens of milliseconds of load before its clocks have ramped up; the
+    # default warm-up is ~0.1 s of steps
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,11 +151,11 @@ def main():
     value = ops / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel durations: the same launches again, each bracketed by HIP events ----
-    iters = max(20, min(args.steps, 200))
+    iters = max(20, min(args.steps, 300))
     per = {}
     for name, fn in (("quant", quant_stage), ("gemm", gemm_stage), ("delta", delta_stage),
                      ("pack", pack_stage)):
-        for _ in range(5):
+        for _ in range(min(args.warmup, 300)):
             fn()
         t = event_times_us(fn, iters)
         per[name] = {"avg_us": sum(t) / len(t), "min_us": min(t)}

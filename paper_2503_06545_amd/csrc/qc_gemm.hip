@@ -109,6 +109,22 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     tile_of_block(blockIdx.x, gridDim.x, a.m_tiles, a.n_tiles, mt, nt);
 
     const int stages = a.KF / 2;
+    // The epilogue's scales and bias are fetched now (one value per thread) and handed round
+    // through LDS after the main loop, so that the epilogue does not start with a chain of L2
+    // round trips.
+    float *lds_sx = reinterpret_cast<float *>(lds + kStages * L::kBytes);  // 256 token scales
+    float *lds_sw = lds_sx + kTileM;                                       // 128 channel scales
+    float *lds_bs = lds_sw + kTileN;                                       // 128 biases
+    float my_sx = 0.0f, my_sw = 0.0f, my_bs = 0.0f;
+    if (OUT != QC_OUT_I32_ACC) {
+        my_sx = a.x_scale[(int64_t)mt * kTileM + threadIdx.x];  // x_scale is padded to Mp
+        const int64_t n = (int64_t)nt * kTileN + threadIdx.x;
+        if (threadIdx.x < kTileN && n < a.N) {
+            my_sw = a.w_scale[n];
+            if (BITS == 4) my_sw *= 0.0625f;  // operands carry codes times 16
+            if (a.bias) my_bs = a.bias[n];
+        }
+    }
     // Weight fragments this wavefront copies HBM -> LDS, at stage 0.
     const uint8_t *wsrc[FPW];
 #pragma unroll
@@ -266,6 +282,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 #undef QC_ISSUE_X
 #undef QC_GLOBAL_LOAD
 
+    // park the scales (fetched at kernel start, long since arrived) where every lane can pick
+    // the ones of its tokens and channels
+    if (OUT != QC_OUT_I32_ACC) {
+        lds_sx[threadIdx.x] = my_sx;
+        if (threadIdx.x < kTileN) { lds_sw[threadIdx.x] = my_sw; lds_bs[threadIdx.x] = my_bs; }
+        __syncthreads();
+    }
+
     // ---- epilogue: registers -> Y --------------------------------------------------------
     // Lane (c = lane % 32, h = lane / 32) of MFMA tile (i, t) holds, in register r, token
     // m0 + 32 i + 8 (r / 4) + 4 h + r % 4 and channel n0 + 4 c + t.
@@ -275,29 +299,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     if (n0 >= a.N) return;
     const bool full = (a.N % 4) == 0 && n0 + 4 <= a.N;
 
-    float sw[4], bs[4];
+    float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f};
     if (OUT != QC_OUT_I32_ACC) {
-        if (full) {
-            const float4 s4 = *reinterpret_cast<const float4 *>(a.w_scale + n0);
-            sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
-            if (a.bias) {
-                const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + n0);
-                bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
-            } else {
-                bs[0] = bs[1] = bs[2] = bs[3] = 0.0f;
-            }
-        } else {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bool in = n0 + t < a.N;
-                sw[t] = in ? a.w_scale[n0 + t] : 0.0f;
-                bs[t] = (in && a.bias) ? a.bias[n0 + t] : 0.0f;
-            }
-        }
-        if (BITS == 4) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) sw[t] *= 0.0625f;  // operands carried codes times 16
-        }
+        const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 4 * c);
+        const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 4 * c);
+        sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
+        bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
     }
 
 #pragma unroll
@@ -308,7 +315,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
             if (m4 >= a.M) continue;
             float sx[4] = {0.f, 0.f, 0.f, 0.f};
             if (OUT != QC_OUT_I32_ACC) {
-                const float4 x4 = *reinterpret_cast<const float4 *>(a.x_scale + m4);
+                const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * 64 + 4 * h + 32 * i + 8 * g);
                 sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
             }
 #pragma unroll
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 template <int BITS, int OUT, int EPI>
 hipError_t launch_variant(const GemmArgs &args, hipStream_t stream) {
     using L = StageLayout<BITS>;
-    constexpr int kLds = kStages * L::kBytes;
+    constexpr int kLds = kStages * L::kBytes + (kTileM + 2 * kTileN) * (int)sizeof(float);
     static bool configured = false;  // a per-function attribute; setting it twice is harmless
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, OUT, EPI>),
