@@ -2,9 +2,9 @@
 // parameters computed online; Section 3.1 Eq. (3)-(4) in symmetric signed form).
 //
 // HBM-bound: every element of X is read once and one int8 code is written.  A row is held in
-// registers between the absmax pass and the cast, so there is no second read.  One wavefront
-// per block and several blocks per CU, so that the load, arithmetic and store phases of
-// different blocks overlap.
+// registers between the absmax pass and the cast, so there is no second read.  Blocks are
+// small (one wavefront per 1152 columns of 8 rows) and many per CU, so that the load,
+// arithmetic and store phases of different blocks overlap.
 //
 // The quotient x / s is the correctly rounded IEEE one, computed without a division per
 // element: with r = 1 / s (one true division per row), q0 = x * r and two residual
@@ -16,10 +16,9 @@
 namespace qc {
 namespace {
 
-constexpr int kThreads = 64;        // one wavefront per block
 constexpr int kGenericThreads = 256;
 constexpr int kUnit = 16;          // elements handled as one unit: 16 codes = one 16 B store
-constexpr int kUnitsPerThread = 9; // a row is spread over TPR lanes, <= 9 units each
+constexpr int kUnitsPerThread = 9; // units held by one lane
 
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
@@ -94,17 +93,24 @@ __device__ inline uint32_t codes4(float q0, float q1, float q2, float q3) {
 
 __device__ inline float scale_of(float absmax) { return fmaxf(absmax, kAbsmaxFloor) / 127.0f; }
 
-// TPR lanes share a row; rows per block = 64 / TPR.  Needs K % 16 == 0 and
-// K / 16 <= TPR * kUnitsPerThread.
-template <typename XT, int TPR>
-__global__ __launch_bounds__(kThreads) void quant_rows_kernel(const XT *__restrict__ X, int64_t M,
-                                                              int64_t K, int8_t *__restrict__ qx,
-                                                              uint8_t *__restrict__ qx_tiled,
-                                                              int64_t KF,
-                                                              float *__restrict__ x_scale) {
-    constexpr int kRowsPerBlock = kThreads / TPR;
-    const int sub = threadIdx.x % TPR;
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / TPR;
+// 8 lanes share a row and a wavefront holds 8 rows x 1152 columns (72 units of 16, 9 per lane)
+// in registers, so that every 16 B store of the fragment layout completes a 128 B line (8 rows
+// x 16 B) within one instruction.  Longer rows are cut into column slices of 1152, one
+// wavefront of the block per slice; the slices agree on the row absmax through LDS.  Needs
+// K % 16 == 0 and K <= 8 slices.
+constexpr int kLanesPerRow = 8;
+constexpr int kRowsPerBlock = 64 / kLanesPerRow;
+constexpr int kUnitsPerSlice = kLanesPerRow * kUnitsPerThread;  // 72 units = 1152 columns
+constexpr int kMaxSlices = 8;
+
+template <typename XT>
+__global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
+    const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale) {
+    __shared__ float slice_max[kMaxSlices][kRowsPerBlock];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6, slices = blockDim.x >> 6;
+    const int sub = lane % kLanesPerRow, row_in_block = lane / kLanesPerRow;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + row_in_block;
     const int units = (int)(K / kUnit);
     const bool live = row < M;
     const XT *xrow = X + (live ? row : 0) * K;
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(const XT *__restri
     Unit<XT> u[kUnitsPerThread];
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
-        const int ui = i * TPR + sub;
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
         if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
         else u[i].zero();
     }
@@ -123,11 +129,16 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(const XT *__restri
 #pragma unroll
         for (int e = 0; e < kUnit; ++e) a = fmaxf(a, fabsf(u[i].get(e)));
 #pragma unroll
-    for (int d = 1; d < TPR; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    for (int d = 1; d < kLanesPerRow; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    if (slices > 1) {  // uniform over the block
+        if (sub == 0) slice_max[slice][row_in_block] = a;
+        __syncthreads();
+        for (int sl = 0; sl < slices; ++sl) a = fmaxf(a, slice_max[sl][row_in_block]);
+    }
 
     const float s = scale_of(a);
     const float r = 1.0f / s;  // correctly rounded
-    if (live && sub == 0) x_scale[row] = s;
+    if (live && sub == 0 && slice == 0) x_scale[row] = s;
     if (!live) return;
 
     int8_t *out_rows = qx ? qx + row * K : nullptr;
@@ -135,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void quant_rows_kernel(const XT *__restri
                                   : nullptr;
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
-        const int ui = i * TPR + sub;
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
         if (ui >= units) continue;
         uint32_t w[4];
 #pragma unroll
@@ -181,24 +192,17 @@ template <typename XT>
 hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
                         int64_t KF, float *x_scale, hipStream_t stream) {
     const int64_t units = K / kUnit;
-    const bool vec = (K % kUnit == 0) && units <= 64 * kUnitsPerThread;
+    const int64_t slices = (units + kUnitsPerSlice - 1) / kUnitsPerSlice;
+    const bool vec = (K % kUnit == 0) && slices <= kMaxSlices;
     if (!vec) {
         const int64_t blocks = (M + 3) / 4;
         quant_rows_generic_kernel<XT><<<dim3((unsigned)blocks), dim3(kGenericThreads), 0, stream>>>(
             X, M, K, qx, qx_tiled, KF, x_scale);
         return hipGetLastError();
     }
-#define QC_LAUNCH_TPR(TPR)                                                                   \
-    do {                                                                                     \
-        const int64_t blocks = (M + (kThreads / TPR) - 1) / (kThreads / TPR);                \
-        quant_rows_kernel<XT, TPR><<<dim3((unsigned)blocks), dim3(kThreads), 0, stream>>>(   \
-            X, M, K, qx, qx_tiled, KF, x_scale);                                             \
-    } while (0)
-    if (units <= 8 * kUnitsPerThread) QC_LAUNCH_TPR(8);
-    else if (units <= 16 * kUnitsPerThread) QC_LAUNCH_TPR(16);
-    else if (units <= 32 * kUnitsPerThread) QC_LAUNCH_TPR(32);
-    else QC_LAUNCH_TPR(64);
-#undef QC_LAUNCH_TPR
+    const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
+    quant_rows_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+        X, M, K, qx, qx_tiled, KF, x_scale);
     return hipGetLastError();
 }
 
