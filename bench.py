@@ -27,9 +27,10 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
 
-# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this
-# script (profiles/), scaled by the same counters on a plain copy; None = not collected yet.
-MEASURED_TRAFFIC_BYTES = {"gemm": None, "quant": None, "delta": None}
+# Bytes per launch between L2 and the fabric (Infinity Cache / HBM) from `rocprofv3 --pmc
+# FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this script, scaled by the same counters on a plain
+# 256 MiB copy (profiles/bench_qkv256_rocprofv3.txt).
+MEASURED_TRAFFIC_BYTES = {"gemm": 166.3e6, "quant": 56.9e6, "delta": 33.6e6}
 
 
 def event_times_us(fn, iters):
@@ -78,6 +79,9 @@ def main():
     # default warm-up is ~0.1 s of steps
     ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a few plain 256 MiB device copies, as the reference kernel "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by token "
@@ -150,15 +154,32 @@ def main():
     ops = 2.0 * M * N * K
     value = ops / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel durations: the same launches again, each bracketed by HIP events ----
-    iters = max(20, min(args.steps, 300))
+    # ---- per-kernel durations: HIP events around batches of back-to-back launches --------
+    # (a batch keeps the GPU loaded and amortises the dispatch gap that an event pair around a
+    # single launch would include; duration = batch time / launches)
+    batch, rounds = 20, max(3, min(args.steps, 600) // 20)
     per = {}
     for name, fn in (("quant", quant_stage), ("gemm", gemm_stage), ("delta", delta_stage),
                      ("pack", pack_stage)):
         for _ in range(min(args.warmup, 300)):
-            fn()
-        t = event_times_us(fn, iters)
+            step()
+        t = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(batch):
+                fn()
+            e1.record()
+            e1.synchronize()
+            t.append(e0.elapsed_time(e1) * 1e3 / batch)
         per[name] = {"avg_us": sum(t) / len(t), "min_us": min(t)}
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     gemm_us = per["gemm"]["avg_us"]
     gemm_tops = ops / (gemm_us * 1e-6) / 1e12

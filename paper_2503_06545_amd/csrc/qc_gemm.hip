@@ -15,7 +15,8 @@
 // under the MFMAs of the current 32 k.  Tokens are the MFMA "A" operand (rows of the result
 // tile) and channels the "B" operand (columns = lanes); the weight row permutation makes a
 // lane's four tiles four consecutive channels, so half a wavefront stores 128 consecutive
-// channels of one token at a time.
+// channels of one token at a time.  The output is written with non-temporal stores: it is not
+// read again by this kernel and would otherwise push the operand panels out of the L2.
 #include <type_traits>
 
 #include "qc_internal.h"
@@ -26,6 +27,8 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                         for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
                     }
                     if (full) {
-                        *reinterpret_cast<int4 *>(y) = make_int4(raw[0], raw[1], raw[2], raw[3]);
+                        __builtin_nontemporal_store(v4i{raw[0], raw[1], raw[2], raw[3]}, reinterpret_cast<v4i *>(y));
                     } else {
 #pragma unroll
                         for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                     if (OUT == QC_OUT_F32) {
                         float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
                         if (full) {
-                            *reinterpret_cast<float4 *>(y) = make_float4(v[0], v[1], v[2], v[3]);
+                            __builtin_nontemporal_store(f4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f4 *>(y));
                         } else {
 #pragma unroll
                             for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                         uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
                         const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
                         if (full) {
-                            *reinterpret_cast<uint2 *>(y) = make_uint2(lo, hi);
+                            __builtin_nontemporal_store(u2{lo, hi}, reinterpret_cast<u2 *>(y));
                         } else {
                             if (n0 + 0 < a.N) y[0] = (uint16_t)(lo & 0xffffu);
                             if (n0 + 1 < a.N) y[1] = (uint16_t)(lo >> 16);
