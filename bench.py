@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized-linear hot path on one MI355X.
 
-A step is one pass of the per-step hot path over one batch of seeded synthetic input:
-qc_qlinear (per-token activation quantization + int8 MFMA GEMM + dequant/bias epilogue) on
-the STDiT QKV projection of a 256x256 video (X bf16 [16384, 1152], W int8 [3456, 1152],
-bf16 out) followed by qc_latent_delta on two [16, 4, 16, 64, 64] float latents.  The weight
-is packed once before the timed region (it is an offline step of the method); its time is
-reported beside the result.  Inputs are resident in HBM when timing starts.
+A step is one pass of the per-step hot path over one batch of seeded synthetic input.  The
+default workload is the STDiT QKV projection of a 256x256 video (X bf16 [16384, 1152],
+W int8 [3456, 1152], bf16 out): qc_qlinear (per-token activation quantization + int8 MFMA
+GEMM + dequant/bias epilogue) followed by qc_latent_delta on two [16, 4, 16, 64, 64] float
+latents.  `--workload` selects the other STDiT layers (fc1+GELU, fc2 with int8 or int4
+weights) or the 28-block sweep (112 qc_qlinear calls, per-layer bit-width from the seeded
+importance mask).  Weights are packed once before the timed region (an offline step of the
+method); the packing time is reported beside the result.  Inputs are resident in HBM when
+timing starts.
 
-Prints ONE JSON line.  `value` = 2*M*N*K integer ops of the step divided by the step time.
-`roofline` describes the dominant kernel (the GEMM), timed with HIP events in a second pass
-over the same launches; `kernels` adds the HBM-bound kernels; `cpu_baseline` is the CPU
+Prints ONE JSON line.  `value` = integer ops (2*M*N*K per layer) of the step divided by the
+step time.  `roofline` describes the dominant kernel (the GEMM), timed with HIP events around
+batches of its launches; `kernels` adds the HBM-bound kernels; `cpu_baseline` is the CPU
 oracle timed on this host's cores on a bounded row sample of the same workload.
 """
 from __future__ import annotations
@@ -29,55 +32,78 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
 
 # Bytes per launch between L2 and the fabric (Infinity Cache / HBM) from `rocprofv3 --pmc
 # FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this script, scaled by the same counters on a plain
-# 256 MiB copy (profiles/bench_qkv256_rocprofv3.txt).
-MEASURED_TRAFFIC_BYTES = {"gemm": 166.3e6, "quant": 56.9e6, "delta": 33.6e6}
+# 256 MiB copy (profiles/bench_qkv256_rocprofv3.txt).  Only collected for the default workload.
+MEASURED_TRAFFIC_BYTES = {"qkv256": {"gemm": 166.3e6, "quant": 56.9e6, "delta": 33.6e6}}
+
+WORKLOADS = ("qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4", "sweep28")
 
 
-def event_times_us(fn, iters):
-    """Per-launch durations of fn() measured with HIP events on the current stream."""
+def batch_times_us(fn, batch, rounds):
+    """Average duration of one fn() from HIP events around batches of back-to-back calls
+    (a batch keeps the GPU loaded and amortises the dispatch gap that an event pair around a
+    single launch would include)."""
     import torch
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
-    for i in range(iters):
-        starts[i].record()
-        fn()
-        stops[i].record()
-    torch.cuda.synchronize()
-    return [starts[i].elapsed_time(stops[i]) * 1e3 for i in range(iters)]
+    t = []
+    for _ in range(rounds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(batch):
+            fn()
+        e1.record()
+        e1.synchronize()
+        t.append(e0.elapsed_time(e1) * 1e3 / batch)
+    return {"avg_us": sum(t) / len(t), "min_us": min(t)}
 
 
 def cpu_baseline(case, target_seconds=15.0):
     """The oracle as it stands on a bounded sample of token rows (all N, all K)."""
-    import numpy as np
     import oracle
     W, b = case.weight(), case.bias()
     qw, sw = oracle.quant_weight(W, case.bits)
+    epi = {"none": oracle.EPI_NONE, "gelu_tanh": oracle.EPI_GELU_TANH,
+           "gelu_erf": oracle.EPI_GELU_ERF}[case.epi]
     threads = oracle.num_threads()
     probe_rows = 64
     x = case.x_rows(0, probe_rows)
     t0 = time.perf_counter()
-    oracle.qlinear(x, qw, sw, b)
+    oracle.qlinear(x, qw, sw, b, epi)
     per_row = (time.perf_counter() - t0) / probe_rows
     rows = int(min(case.M, max(probe_rows, target_seconds / per_row)))
     rows -= rows % 64
     x = case.x_rows(0, rows)
     t0 = time.perf_counter()
-    oracle.qlinear(x, qw, sw, b)
+    oracle.qlinear(x, qw, sw, b, epi)
     dt = time.perf_counter() - t0
     tops = 2.0 * rows * case.N * case.K / dt / 1e12
     return {"value": tops, "unit": "TOPS", "cores": threads, "kind": "oracle",
-            "sample": f"first {rows} of {case.M} token rows x all N={case.N} x K={case.K} "
-                      f"(quantize + int32 GEMM + epilogue), {dt:.2f} s, OpenMP over rows",
+            "sample": f"first {rows} of {case.M} token rows x all N={case.N} x K={case.K} of "
+                      f"layer {case.name} (quantize + int32 GEMM + epilogue), {dt:.2f} s, "
+                      f"OpenMP over rows",
             "seconds": dt}
+
+
+class Layer:
+    """Device buffers of one quantized linear."""
+
+    def __init__(self, case, x, ws, Y, layer_index=0):
+        import torch
+        from paper_2503_06545_amd import binding as qc
+        self.case, self.x, self.ws, self.Y = case, x, ws, Y
+        self.W = torch.from_numpy(case.weight(layer_index)).cuda()
+        self.bias = torch.from_numpy(case.bias(layer_index)).cuda()
+        self.pw = qc.pack_weight_t(self.W, case.bits)
+        self.epi = qc.EPI[case.epi]
+        self.ops = 2.0 * case.M * case.N * case.K
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--steps", type=int, default=None)
     # the GPU needs some tens of milliseconds of load before its clocks have ramped up; the
     # default warm-up is ~0.1 s of steps
-    ap.add_argument("--warmup", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", choices=WORKLOADS, default="qkv256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 256 MiB device copies, as the reference kernel "
@@ -98,81 +124,120 @@ def main():
         return 2
     qc.lib()  # fail loudly if libqc.so is missing
 
-    case = synth.QKV_256
-    M, K, N = case.M, case.K, case.N
-    x = torch.from_numpy(case.x().view(np.int16)).cuda().view(torch.bfloat16)
-    W = torch.from_numpy(case.weight()).cuda()
-    bias = torch.from_numpy(case.bias()).cuda()
+    def to_dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- workload ------------------------------------------------------------------------
+    sweep = args.workload == "sweep28"
+    if sweep:
+        cases = synth.stdit_block_layers()
+        describe = ("28 STDiT blocks x (QKV 1152->3456, out 1152->1152, fc1 1152->4608 + GELU, "
+                    "fc2 4608->1152), M = 131072 tokens (CFG batch 2 at 512x512), bf16 in/out, "
+                    "per-layer weight bit-width from the seeded mask")
+        default_steps, default_warmup = 20, 4
+    else:
+        case0 = {"qkv256": synth.QKV_256, "fc1_512": synth.FC1_512, "fc2_512_w8": synth.FC2_512_W8,
+                 "fc2_512_w4": synth.FC2_512_W4}[args.workload]
+        cases = [case0]
+        describe = {
+            "qkv256": "STDiT QKV projection 256x256 (BASELINE configs[1]): X bf16 [16384,1152] "
+                      "N(0,1) with 12 outlier columns x20, W8A8 [3456,1152], bias, bf16 out",
+            "fc1_512": "STDiT MLP fc1 + GELU(tanh) 512x512 (BASELINE configs[2]): X bf16 "
+                       "[65536,1152], W8A8 [4608,1152], bf16 out",
+            "fc2_512_w8": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] "
+                          "post-GELU, W8A8 [1152,4608], bf16 out",
+            "fc2_512_w4": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] "
+                          "post-GELU, W4A8 [1152,4608] int4 weights, bf16 out",
+        }[args.workload] + "; + latent delta on 2 x [16,4,16,64,64] fp32"
+        scale = max(1, (case0.M * case0.N * case0.K) // (16384 * 3456 * 1152))
+        default_steps, default_warmup = max(200, 3000 // scale), max(100, 1000 // scale)
+    steps = args.steps if args.steps is not None else default_steps
+    warmup = args.warmup if args.warmup is not None else default_warmup
+
+    # one activation tensor per distinct (K, distribution), shared by the layers that use it
+    x_cache, layers = {}, []
+    M = cases[0].M
+    maxK = max(c.K for c in cases)
+    maxN = max(c.N for c in cases)
+    ws = qc.qlinear_workspace_t(M, maxK, maxN)
+    Y = torch.empty(M * maxN, dtype=torch.bfloat16, device="cuda")
+    for i, c in enumerate(cases):
+        key = (c.K, c.post_gelu, c.outliers)
+        if key not in x_cache:
+            x_cache[key] = to_dev_bf16(c.x())
+        layers.append(Layer(c, x_cache[key], ws, Y, layer_index=i))
+    w4_layers = sum(c.bits == 4 for c in cases)
+
     cur_h, prev_h = synth.latent_pair(seed=0)
     cur, prev = torch.from_numpy(cur_h).cuda(), torch.from_numpy(prev_h).cuda()
     n_lat = cur.numel()
-
-    pw = qc.pack_weight_t(W, case.bits)
-    ws = qc.qlinear_workspace_t(M, K, N)
     dws = qc.latent_delta_workspace_t(n_lat)
-    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     out3 = torch.empty(3, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    epi = qc.EPI[case.epi]
 
     def check(st):
         if st != qc.QC_OK:
             raise qc.QcError(st, "bench step")
 
-    def step():
-        check(qc.qc_qlinear(x.data_ptr(), qc.QC_BF16, M, K, pw.blob.data_ptr(), pw.scale.data_ptr(),
-                            case.bits, N, bias.data_ptr(), epi, Y.data_ptr(), qc.QC_OUT_BF16,
-                            ws.data_ptr(), ws.numel(), stream))
-        check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
-                                 dws.data_ptr(), dws.numel(), stream))
+    def qlinear(L):
+        c = L.case
+        check(qc.qc_qlinear(L.x.data_ptr(), qc.QC_BF16, c.M, c.K, L.pw.blob.data_ptr(),
+                            L.pw.scale.data_ptr(), c.bits, c.N, L.bias.data_ptr(), L.epi,
+                            L.Y.data_ptr(), qc.QC_OUT_BF16, L.ws.data_ptr(), L.ws.numel(), stream))
 
-    def quant_stage():
-        check(qc.qc_qlinear_quant(x.data_ptr(), qc.QC_BF16, M, K, ws.data_ptr(), ws.numel(), stream))
+    def quant_stage(L):
+        c = L.case
+        check(qc.qc_qlinear_quant(L.x.data_ptr(), qc.QC_BF16, c.M, c.K, L.ws.data_ptr(),
+                                  L.ws.numel(), stream))
 
-    def gemm_stage():
-        check(qc.qc_qlinear_gemm(ws.data_ptr(), ws.numel(), M, K, pw.blob.data_ptr(),
-                                 pw.scale.data_ptr(), case.bits, N, bias.data_ptr(), epi,
-                                 Y.data_ptr(), qc.QC_OUT_BF16, stream))
+    def gemm_stage(L):
+        c = L.case
+        check(qc.qc_qlinear_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K, L.pw.blob.data_ptr(),
+                                 L.pw.scale.data_ptr(), c.bits, c.N, L.bias.data_ptr(), L.epi,
+                                 L.Y.data_ptr(), qc.QC_OUT_BF16, stream))
 
     def delta_stage():
         check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
                                  dws.data_ptr(), dws.numel(), stream))
 
-    def pack_stage():
-        check(qc.qc_pack_weight(W.data_ptr(), N, K, case.bits, pw.blob.data_ptr(),
-                                pw.scale.data_ptr(), stream))
+    def pack_stage(L):
+        c = L.case
+        check(qc.qc_pack_weight(L.W.data_ptr(), c.N, c.K, c.bits, L.pw.blob.data_ptr(),
+                                L.pw.scale.data_ptr(), stream))
+
+    def step():
+        for L in layers:
+            qlinear(L)
+        if not sweep:
+            delta_stage()
 
     # ---- headline: K steps between two full synchronisations ----------------------------
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    ops = 2.0 * M * N * K
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    ops = sum(L.ops for L in layers)
     value = ops / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel durations: HIP events around batches of back-to-back launches --------
-    # (a batch keeps the GPU loaded and amortises the dispatch gap that an event pair around a
-    # single launch would include; duration = batch time / launches)
-    batch, rounds = 20, max(3, min(args.steps, 600) // 20)
-    per = {}
-    for name, fn in (("quant", quant_stage), ("gemm", gemm_stage), ("delta", delta_stage),
-                     ("pack", pack_stage)):
-        for _ in range(min(args.warmup, 300)):
-            step()
-        t = []
-        for _ in range(rounds):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(batch):
-                fn()
-            e1.record()
-            e1.synchronize()
-            t.append(e0.elapsed_time(e1) * 1e3 / batch)
-        per[name] = {"avg_us": sum(t) / len(t), "min_us": min(t)}
+    # ---- per-kernel durations --------------------------------------------------------------
+    if sweep:
+        batch, rounds = 1, 3
+    else:
+        batch = 20
+        rounds = max(3, min(steps, 600) // batch)
+    for _ in range(min(warmup, 300)):
+        step()
+    per = {
+        "quant": batch_times_us(lambda: [quant_stage(L) for L in layers], batch, rounds),
+        "gemm": batch_times_us(lambda: [gemm_stage(L) for L in layers], batch, rounds),
+        "pack": batch_times_us(lambda: [pack_stage(L) for L in layers], 1, 5),
+    }
+    if not sweep:
+        per["delta"] = batch_times_us(delta_stage, batch, rounds)
 
     if args.calibration_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -181,51 +246,60 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {})
     gemm_us = per["gemm"]["avg_us"]
     gemm_tops = ops / (gemm_us * 1e-6) / 1e12
-    quant_bytes = M * K * 2 + M * K + 4 * M
-    delta_bytes = 2 * n_lat * 4 + 12
+    quant_bytes = sum(c.M * c.K * 3 + 4 * c.M for c in cases)
     quant_gbs = quant_bytes / (per["quant"]["avg_us"] * 1e-6) / 1e9
-    delta_gbs = delta_bytes / (per["delta"]["avg_us"] * 1e-6) / 1e9
+    kernel_name = ("gemm_kernel<8|4, bf16, none|gelu_tanh> (112 launches)" if sweep else
+                   f"gemm_kernel<{cases[0].bits}, bf16, {cases[0].epi}>")
 
     result = {
-        "metric": "quantized-linear int8 TOPS, whole qc_qlinear + qc_latent_delta step, 1 MI355X",
+        "metric": "quantized-linear int8 TOPS, whole qc_qlinear" +
+                  ("" if sweep else " + qc_latent_delta") + " step, 1 MI355X",
         "value": round(value, 2),
         "unit": "TOPS",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; bf16 in/out, fp32 scales)",
         "data": "synthetic",
-        "config": {"workload": "STDiT QKV projection 256x256 (BASELINE configs[1]): X bf16 "
-                               "[16384,1152] N(0,1) with 12 outlier columns x20, W8A8 [3456,1152], "
-                               "bias, bf16 out; + latent delta on 2 x [16,4,16,64,64] fp32",
-                   "M": M, "K": K, "N": N, "weight_bits": case.bits, "seed": case.seed,
+        "config": {"workload": describe, "name": args.workload, "layers": len(cases),
+                   "w4_layers": w4_layers, "M": M, "seed": cases[0].seed,
                    "offline_not_in_step": "qc_pack_weight"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<8, bf16, none>",
+        "roofline": {"bound": "mfma", "kernel": kernel_name,
                      "achieved": round(gemm_tops, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES["gemm"],
-                     "ops_per_launch": ops, "avg_launch_us": round(gemm_us, 2)},
+                     "traffic": traffic.get("gemm"),
+                     "ops_per_launch": ops / len(cases), "launches_per_step": len(cases),
+                     "avg_launch_us": round(gemm_us / len(cases), 2)},
         "kernels": {
             "quant_act": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": PEAK_HBM_GBS,
                           "unit": "GB/s", "frac": round(quant_gbs / PEAK_HBM_GBS, 4),
-                          "bytes_per_launch": quant_bytes, "avg_launch_us": round(per["quant"]["avg_us"], 2),
-                          "traffic": MEASURED_TRAFFIC_BYTES["quant"]},
-            "latent_delta": {"bound": "hbm", "achieved": round(delta_gbs, 1), "peak": PEAK_HBM_GBS,
-                             "unit": "GB/s", "frac": round(delta_gbs / PEAK_HBM_GBS, 4),
-                             "bytes_per_launch": delta_bytes, "avg_launch_us": round(per["delta"]["avg_us"], 2),
-                             "note": "33.5 MB of inputs stay resident in the 256 MB Infinity Cache between launches (warm)",
-                             "traffic": MEASURED_TRAFFIC_BYTES["delta"]},
-            "pack_weight_offline": {"avg_launch_us": round(per["pack"]["avg_us"], 2)},
+                          "bytes_per_launch": quant_bytes / len(cases),
+                          "avg_launch_us": round(per["quant"]["avg_us"] / len(cases), 2),
+                          "traffic": traffic.get("quant")},
+            "pack_weight_offline": {"avg_launch_us": round(per["pack"]["avg_us"] / len(cases), 2)},
         },
     }
+    if not sweep:
+        c = cases[0]
+        result["config"].update({"K": c.K, "N": c.N, "weight_bits": c.bits, "epilogue": c.epi})
+        delta_bytes = 2 * n_lat * 4 + 12
+        delta_gbs = delta_bytes / (per["delta"]["avg_us"] * 1e-6) / 1e9
+        result["kernels"]["latent_delta"] = {
+            "bound": "hbm", "achieved": round(delta_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(delta_gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": delta_bytes,
+            "avg_launch_us": round(per["delta"]["avg_us"], 2),
+            "note": "two launches per call; the 33.5 MB of inputs stay resident in the 256 MB "
+                    "Infinity Cache between calls (warm)",
+            "traffic": traffic.get("delta")}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case)
+        result["cpu_baseline"] = cpu_baseline(cases[0])
     print(json.dumps(result))
     return 0
 

@@ -52,10 +52,19 @@ def outlier_columns(seed: int, K: int, count: int) -> np.ndarray:
     return np.sort(_rng(seed, TID_OUTLIER, 0).choice(K, size=count, replace=False))
 
 
-def _gelu_tanh_f64(v: np.ndarray) -> np.ndarray:
+def _gelu_tanh_f32(v: np.ndarray) -> np.ndarray:
     # Only shapes the *input distribution* of the fc2 layer (post-GELU activations).
-    c = math.sqrt(2.0 / math.pi)
-    return 0.5 * v * (1.0 + np.tanh(c * (v + 0.044715 * v ** 3)))
+    c = np.float32(math.sqrt(2.0 / math.pi))
+    t = v * v
+    t *= np.float32(0.044715)
+    t += np.float32(1.0)
+    t *= v
+    t *= c
+    np.tanh(t, out=t)
+    t += np.float32(1.0)
+    t *= v
+    t *= np.float32(0.5)
+    return t
 
 
 @dataclass(frozen=True)
@@ -77,14 +86,17 @@ class LinearCase:
         """Rows of X as float32 (x_dtype f32) or bf16 bit patterns uint16 (x_dtype bf16)."""
         x = normal_rows(self.seed, TID_X, row0, row1, self.K)
         if self.post_gelu:
-            x = _gelu_tanh_f64(x.astype(np.float64)).astype(np.float32)
+            x = _gelu_tanh_f32(x)
         if self.outliers:
             cols = outlier_columns(self.seed, self.K, self.outliers)
             x[:, cols] *= np.float32(20.0)
         return to_bf16_bits(x) if self.x_dtype == "bf16" else x
 
     def x(self) -> np.ndarray:
-        return self.x_rows(0, self.M)
+        """All of X, generated in row chunks to bound the temporaries."""
+        chunk = 8192
+        parts = [self.x_rows(r, min(self.M, r + chunk)) for r in range(0, self.M, chunk)]
+        return parts[0] if len(parts) == 1 else np.concatenate(parts, axis=0)
 
     def weight(self, layer: int = 0) -> np.ndarray:
         """W float32 [N, K] ~ N(0, std 0.02)."""
