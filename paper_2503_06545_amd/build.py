@@ -12,6 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqc.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["qc_api.hip", "qc_quant.hip", "qc_pack.hip", "qc_gemm.hip", "qc_delta.hip"]
+ROOFS = os.path.join(HERE, "qc_roofs")  # stand-alone roofline micro-benchmark
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -29,11 +30,18 @@ def _compile(src: str) -> str:
     return obj
 
 
+def _compile_roofs(_=None) -> str:
+    subprocess.run([HIPCC, *FLAGS, os.path.join(CSRC, "qc_roofs.hip"), "-o", ROOFS], check=True)
+    return ROOFS
+
+
 def build(verbose: bool = True) -> str:
-    """Always recompiles every source and relinks libqc.so."""
+    """Always recompiles every source, relinks libqc.so and rebuilds the qc_roofs program."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as pool:
+        roofs = pool.submit(_compile_roofs)
         objs = list(pool.map(_compile, SOURCES))
+        roofs.result()
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], check=True)
     if verbose:
         print(f"built {LIB}", file=sys.stderr)

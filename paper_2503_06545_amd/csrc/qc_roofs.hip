@@ -1,0 +1,256 @@
+// qc_roofs: measures the roofs this GPU actually sustains, next to which the kernels of
+// libqc are judged: streaming HBM bandwidth, the int8 MFMA issue rate with all-zero and with
+// random operands (the chip is power limited: the clock it holds depends on how many bits
+// toggle), the same MFMA loop fed with operand traffic in the proportions of the GEMM kernel,
+// and LDS / L2 delivery rates per CU.  Stand-alone program, no arguments; prints one line per
+// measurement.  Each measurement runs for several tens of milliseconds so that the clocks
+// have settled.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <vector>
+
+#define CK(x)                                                                     \
+    do {                                                                          \
+        hipError_t e_ = (x);                                                      \
+        if (e_ != hipSuccess) {                                                   \
+            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
+            exit(1);                                                              \
+        }                                                                         \
+    } while (0)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// ---- HBM ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ a,
+                                                   float4 *__restrict__ b, int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) b[i] = a[i];
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const float4 *__restrict__ a, float *out,
+                                                   int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    float s = 0;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const float4 v0 = a[i], v1 = a[i + stride], v2 = a[i + 2 * stride], v3 = a[i + 3 * stride];
+        s += v0.x + v1.y + v2.z + v3.w;
+    }
+    if (s == 12345.678f) out[0] = s;
+}
+
+// ---- MFMA with optional operand traffic -----------------------------------------------------
+// per iteration: 16 MFMAs (2 x 8 tiles); LDSR ds_read_b128 per wavefront from LDS; GLD 16 B/lane
+// global loads per wavefront from an L2-resident buffer
+template <int LDSR, int GLD>
+__global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ data,
+                                                      const uint8_t *__restrict__ gsrc, int iters,
+                                                      int *out) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[16384];
+    for (int i = threadIdx.x; i < 16384 / 16; i += 256) ((v4i *)lds)[i] = data[i];
+    __syncthreads();
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v4i a[2], b[8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[i] = data[(threadIdx.x * 4 + i) & 1023];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = data[(threadIdx.x * 8 + i) & 1023];
+    const uint8_t *g = gsrc + ((size_t)(blockIdx.x & 63) * 65536) + wave * 16384 + lane * 16;
+    v4i gx = {0, 0, 0, 0};
+    for (int it = 0; it < iters; ++it) {
+        v4i gl[GLD > 0 ? GLD : 1];
+#pragma unroll
+        for (int j = 0; j < GLD; ++j) gl[j] = *(const v4i *)(g + ((it * GLD + j) & 15) * 1024);
+#pragma unroll
+        for (int j = 0; j < LDSR; ++j) {
+            const v4i v = *(const v4i *)(lds + ((j + it) & 15) * 1024 + lane * 16);
+            if (j < 8) b[j] = v;
+            else a[j & 1] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[t], acc[t], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < GLD; ++j) gx ^= gl[j];
+    }
+    int s = gx[0] ^ gx[1] ^ gx[2] ^ gx[3];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
+    if (s == 0x7fffffff) out[0] = s;
+}
+
+// ---- LDS -------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void lds_read_kernel(int iters, int *out) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[16384];
+    for (int i = threadIdx.x; i < 16384 / 4; i += 1024) ((int *)lds)[i] = i;
+    __syncthreads();
+    const unsigned addr = (threadIdx.x & 63) * 16 + ((threadIdx.x >> 6) & 7) * 1024;
+    v4i a, b, c, d, e, f, g, h;
+    for (int it = 0; it < iters; ++it) {
+        asm volatile(
+            "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:1024\n"
+            "ds_read_b128 %2, %8 offset:2048\n ds_read_b128 %3, %8 offset:3072\n"
+            "ds_read_b128 %4, %8 offset:4096\n ds_read_b128 %5, %8 offset:5120\n"
+            "ds_read_b128 %6, %8 offset:6144\n ds_read_b128 %7, %8 offset:7168\n"
+            "s_waitcnt lgkmcnt(0)\n"
+            : "=v"(a), "=v"(b), "=v"(c), "=v"(d), "=v"(e), "=v"(f), "=v"(g), "=v"(h)
+            : "v"(addr)
+            : "memory");
+    }
+    if (a[0] + b[0] + c[0] + d[0] + e[0] + f[0] + g[0] + h[0] == 0x7fffffff) out[0] = 1;
+}
+
+__global__ __launch_bounds__(512) void lds_write_kernel(int iters, int *out) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t dyn_lds[];
+    const unsigned addr = (threadIdx.x & 63) * 16 + ((threadIdx.x >> 6) & 7) * 8192;
+    const v4i v = {(int)threadIdx.x, 1, 2, 3};
+    for (int it = 0; it < iters; ++it) {
+        asm volatile(
+            "ds_write_b128 %0, %1\n ds_write_b128 %0, %1 offset:1024\n"
+            "ds_write_b128 %0, %1 offset:2048\n ds_write_b128 %0, %1 offset:3072\n"
+            "ds_write_b128 %0, %1 offset:4096\n ds_write_b128 %0, %1 offset:5120\n"
+            "ds_write_b128 %0, %1 offset:6144\n ds_write_b128 %0, %1 offset:7168\n"
+            "s_waitcnt lgkmcnt(0)\n" ::"v"(addr), "v"(v)
+            : "memory");
+    }
+    __syncthreads();
+    if (dyn_lds[threadIdx.x] == 77 && iters < 0) out[0] = 1;
+}
+
+// ---- L2 -> CU ---------------------------------------------------------------------------------
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void l2_load_kernel(const uint8_t *src, int iters, int *out) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint8_t *base = src + (size_t)(blockIdx.x % 16) * 65536;  // 1 MiB hot set
+    v4i acc = {0, 0, 0, 0};
+    for (int it = 0; it < iters; ++it) {
+        v4i v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int chunk = (it * 8 + j) * (THREADS / 64) + wave;
+            v[j] = *(const v4i *)(base + ((size_t)chunk * 1024) % 65536 + lane * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc ^= v[j];
+    }
+    if (acc[0] + acc[1] + acc[2] + acc[3] == 0x12345) out[0] = 1;
+}
+
+template <typename F>
+static float settled_ms(F launch) {
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    float ms = 0, total = 0;
+    while (total < 80.f) {  // let the clocks settle
+        CK(hipEventRecord(e0));
+        launch();
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        total += ms;
+    }
+    float sum = 0;
+    for (int i = 0; i < 3; ++i) {
+        CK(hipEventRecord(e0));
+        launch();
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+        sum += ms;
+    }
+    return sum / 3;
+}
+
+int main() {
+    hipDeviceProp_t prop;
+    CK(hipGetDeviceProperties(&prop, 0));
+    const int CU = prop.multiProcessorCount;
+    const double ghz = 2.4;
+    printf("device %s, %d CUs; per-CU rates below are quoted per clock of a nominal %.1f GHz\n",
+           prop.gcnArchName, CU, ghz);
+    int *dout;
+    CK(hipMalloc(&dout, 64));
+
+    {  // HBM
+        const int64_t n = (int64_t)1 << 30;
+        float4 *a, *b;
+        CK(hipMalloc(&a, n));
+        CK(hipMalloc(&b, n));
+        CK(hipMemset(a, 1, n));
+        CK(hipMemset(b, 2, n));
+        float ms = settled_ms([&] { read_kernel<<<16384, 256>>>(a, (float *)dout, n / 16); });
+        printf("hbm  read-only stream, 1 GiB:            %7.0f GB/s\n", n / ms * 1e-6);
+        ms = settled_ms([&] { copy_kernel<<<65536, 256>>>(a, b, n / 16); });
+        printf("hbm  copy, 1 GiB read + 1 GiB written:   %7.0f GB/s\n", 2.0 * n / ms * 1e-6);
+        CK(hipFree(a));
+        CK(hipFree(b));
+    }
+
+    v4i *d_zero, *d_rand;
+    uint8_t *gsrc;
+    {
+        std::vector<int> h(16384), z(16384, 0);
+        srand(3);
+        for (auto &v : h) {
+            uint32_t w = 0;
+            for (int b = 0; b < 4; ++b) {
+                const int g = (rand() % 41) - 20 + (rand() % 41) - 20;  // spread like weight codes
+                w |= (uint32_t)(uint8_t)(int8_t)g << (8 * b);
+            }
+            v = (int)w;
+        }
+        CK(hipMalloc(&d_zero, 65536));
+        CK(hipMalloc(&d_rand, 65536));
+        CK(hipMemcpy(d_zero, z.data(), 65536, hipMemcpyHostToDevice));
+        CK(hipMemcpy(d_rand, h.data(), 65536, hipMemcpyHostToDevice));
+        std::vector<uint8_t> hg(64 * 65536);
+        for (auto &v : hg) v = rand() & 255;
+        CK(hipMalloc(&gsrc, hg.size()));
+        CK(hipMemcpy(gsrc, hg.data(), hg.size(), hipMemcpyHostToDevice));
+    }
+    const int iters = 20000, blocks = 2 * CU;
+    const double ops = (double)blocks * 4 * iters * 16 * 65536.0;
+    auto tops = [&](float ms) { return ops / ms * 1e-9; };
+    printf("mfma v_mfma_i32_32x32x32_i8, 2 wavefronts/SIMD, registers only, zero operands: %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_zero, gsrc, iters, dout); })));
+    printf("mfma same, random int8 operands:                                               %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma random operands + 0.5 ds_read_b128 per MFMA:                              %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<8, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma random operands + 256 B per MFMA loaded from L2:                          %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<0, 4><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma random operands + 0.5 ds_read_b128 and 384 B from L2 per MFMA (the GEMM): %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<8, 6><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma random operands + 0.5 ds_read_b128 and 128 B from L2 per MFMA:            %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<8, 2><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+
+    {
+        const int li = 20000;
+        float ms = settled_ms([&] { lds_read_kernel<<<CU, 1024>>>(li, dout); });
+        printf("lds  ds_read_b128, 16 wavefronts/CU:   %6.1f B/clk/CU\n",
+               (double)1024 * li * 8 * 16 / (ms * 1e-3) / (ghz * 1e9));
+        ms = settled_ms([&] { lds_write_kernel<<<CU, 512, 65536>>>(li, dout); });
+        printf("lds  ds_write_b128, 8 wavefronts/CU:   %6.1f B/clk/CU\n",
+               (double)512 * li * 8 * 16 / (ms * 1e-3) / (ghz * 1e9));
+        const int di = 4000;
+        ms = settled_ms([&] { l2_load_kernel<256><<<2 * CU, 256>>>(gsrc, di, dout); });
+        printf("l2   global_load_dwordx4, 8 wavefronts/CU:  %6.1f B/clk/CU\n",
+               (double)2 * 256 * di * 8 * 16 / (ms * 1e-3) / (ghz * 1e9));
+        ms = settled_ms([&] { l2_load_kernel<1024><<<CU, 1024>>>(gsrc, di, dout); });
+        printf("l2   global_load_dwordx4, 16 wavefronts/CU: %6.1f B/clk/CU\n",
+               (double)1024 * di * 8 * 16 / (ms * 1e-3) / (ghz * 1e9));
+    }
+    return 0;
+}
