@@ -137,6 +137,21 @@ qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t
                           const void *packed, const float *w_scale, int bits, int64_t N,
                           const float *bias, qc_epilogue epi, void *Y, qc_out ydt, void *stream);
 
+/* ---- activation bit-width as an argument ----------------------------------------------
+ * Section 3.2 AIGQ (2), Eq. (8): the activation bit-width is switched per timestep between
+ * a maximum, a middle and a minimum value; Table 1 reports the W4A6 operating point.  These
+ * variants take it as `act_bits` = 8, 6 or 4: the same quantizer with qmax = 2^(act_bits-1) - 1
+ * (127, 31, 7), codes still stored one per int8, so the GEMM is unchanged.  The calls without
+ * the argument are these with act_bits = 8.  Other values: QC_ERR_UNSUPPORTED. */
+qc_status qc_quant_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                            int8_t *qx, float *x_scale, void *stream);
+qc_status qc_qlinear_quant_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                                void *workspace, size_t workspace_bytes, void *stream);
+qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                              const void *packed, const float *w_scale, int bits, int64_t N,
+                              const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
  * activation codes and scales it used out of the workspace in canonical order:
  * qx int8 [M, K] row major, x_scale float [M]. */

@@ -9,7 +9,8 @@ Paper passages each function follows (arxiv 2503.06545):
   quant_act, quant_weight   Section 3.1 Eq. (3), Eq. (4) in symmetric signed form;
                             Section 4.1 "Quantization Scheme" (per-channel weight,
                             online activation scales); Section 3.2 AIGQ (1) for the
-                            per-layer weight bit-width
+                            per-layer weight bit-width, AIGQ (2) Eq. (8) for the
+                            activation bit-width (8, 6 or 4 in an int8 container)
   gemm_i32, epilogue,       Section 4.1 "Hardware Implementation" (low-bit GEMM with
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
@@ -57,7 +58,7 @@ def _L():
         lib.orc_epilogue_f64.argtypes = [vp, vp, vp, vp, i32, i64, i64, vp]
         lib.orc_round_to_f32.argtypes = [vp, i64, vp]
         lib.orc_round_to_bf16.argtypes = [vp, i64, vp]
-        lib.orc_qlinear.argtypes = [vp, i32, i64, i64, vp, vp, i64, vp, i32, vp, vp, vp, vp]
+        lib.orc_qlinear.argtypes = [vp, i32, i64, i64, i32, vp, vp, i64, vp, i32, vp, vp, vp, vp]
         lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
         for name in ("orc_set_num_threads", "orc_quant_rows_f32", "orc_quant_rows_bf16",
                      "orc_pack_int4", "orc_unpack_int4", "orc_gemm_i32", "orc_gemm_i64",
@@ -105,9 +106,10 @@ def _quant_rows(X, qm):
     return q, s
 
 
-def quant_act(X):
-    """Per-token (per-row) symmetric int8 quantization of activations X [M, K]."""
-    return _quant_rows(X, 127)
+def quant_act(X, act_bits: int = 8):
+    """Per-token (per-row) symmetric quantization of activations X [M, K] into an int8
+    container; act_bits 8, 6 or 4 (Section 3.2 AIGQ (2), Eq. (8))."""
+    return _quant_rows(X, qmax(act_bits))
 
 
 def quant_weight(W, bits: int):
@@ -185,7 +187,7 @@ def bf16_bits_to_f64(bits):
     return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
-def qlinear(X, qw, sw, bias=None, epi=EPI_NONE):
+def qlinear(X, qw, sw, bias=None, epi=EPI_NONE, act_bits: int = 8):
     """Whole quantized linear.  X float32 or uint16(bf16 bits) [M, K]; qw int8 codes [N, K].
 
     Returns dict(qx, sx, acc, y) with y in float64 before the single output rounding.
@@ -201,8 +203,8 @@ def qlinear(X, qw, sw, bias=None, epi=EPI_NONE):
     sx = np.empty((M,), np.float32)
     acc = np.empty((M, N), np.int32)
     y = np.empty((M, N), np.float64)
-    _L().orc_qlinear(_p(X), int(x_is_bf16), M, K, _p(qw), _p(sw), N, _p(bias), int(epi), _p(qx),
-                     _p(sx), _p(acc), _p(y))
+    _L().orc_qlinear(_p(X), int(x_is_bf16), M, K, qmax(act_bits), _p(qw), _p(sw), N, _p(bias),
+                     int(epi), _p(qx), _p(sx), _p(acc), _p(y))
     return {"qx": qx, "sx": sx, "acc": acc, "y": y}
 
 

@@ -204,17 +204,18 @@ void orc_round_to_bf16(const double *y, int64_t count, uint16_t *out) {
 
 /*
  * The whole quantized linear on already quantized weights, as the GPU call
- * sees it: quantize the rows of X, integer GEMM, epilogue.  x_is_bf16 selects
- * how X is read.  Outputs: codes qx [M, K], scales sx [M], accumulators
+ * sees it: quantize the rows of X (act_qmax = 127, or 31 / 7 for the 6- and 4-bit
+ * activations of Section 3.2 AIGQ (2), Eq. (8)), integer GEMM, epilogue.  x_is_bf16
+ * selects how X is read.  Outputs: codes qx [M, K], scales sx [M], accumulators
  * acc [M, N] and y [M, N] in binary64 (the caller rounds once).
  */
-void orc_qlinear(const void *X, int x_is_bf16, int64_t M, int64_t K, const int8_t *qw,
-                 const float *sw, int64_t N, const float *bias, int epi, int8_t *qx, float *sx,
-                 int32_t *acc, double *y) {
+void orc_qlinear(const void *X, int x_is_bf16, int64_t M, int64_t K, int act_qmax,
+                 const int8_t *qw, const float *sw, int64_t N, const float *bias, int epi,
+                 int8_t *qx, float *sx, int32_t *acc, double *y) {
     if (x_is_bf16)
-        orc_quant_rows_bf16((const uint16_t *)X, M, K, 127, qx, sx);
+        orc_quant_rows_bf16((const uint16_t *)X, M, K, act_qmax, qx, sx);
     else
-        orc_quant_rows_f32((const float *)X, M, K, 127, qx, sx);
+        orc_quant_rows_f32((const float *)X, M, K, act_qmax, qx, sx);
     orc_gemm_i32(qx, qw, M, N, K, acc);
     orc_epilogue_f64(acc, sx, sw, bias, epi, M, N, y);
 }

@@ -22,7 +22,8 @@ QC_MAX_K = 131072
 EXPORTS = (
     "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",
     "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
-    "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_debug_workspace_act", "qc_latent_delta",
+    "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_quant_act_bits",
+    "qc_qlinear_quant_bits", "qc_qlinear_act_bits", "qc_debug_workspace_act", "qc_latent_delta",
 )
 
 
@@ -65,6 +66,13 @@ def lib() -> ctypes.CDLL:
         L.qc_qlinear_quant.argtypes = [vp, i32, i64, i64, vp, sz, vp]
         L.qc_qlinear_gemm.restype = i32
         L.qc_qlinear_gemm.argtypes = [vp, sz, i64, i64, vp, vp, i32, i64, vp, i32, vp, i32, vp]
+        L.qc_quant_act_bits.restype = i32
+        L.qc_quant_act_bits.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp]
+        L.qc_qlinear_quant_bits.restype = i32
+        L.qc_qlinear_quant_bits.argtypes = [vp, i32, i64, i64, i32, vp, sz, vp]
+        L.qc_qlinear_act_bits.restype = i32
+        L.qc_qlinear_act_bits.argtypes = [vp, i32, i64, i64, i32, vp, vp, i32, i64, vp, i32, vp, i32,
+                                          vp, sz, vp]
         L.qc_debug_workspace_act.restype = i32
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
@@ -121,6 +129,21 @@ def qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, 
                     stream=0) -> int:
     return int(lib().qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N,
                                      bias, epi, Y, ydt, stream))
+
+
+def qc_quant_act_bits(X, xdt, M, K, act_bits, qx, x_scale, stream=0) -> int:
+    return int(lib().qc_quant_act_bits(X, xdt, M, K, act_bits, qx, x_scale, stream))
+
+
+def qc_qlinear_quant_bits(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_quant_bits(X, xdt, M, K, act_bits, workspace, workspace_bytes,
+                                           stream))
+
+
+def qc_qlinear_act_bits(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                        workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_act_bits(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias,
+                                         epi, Y, ydt, workspace, workspace_bytes, stream))
 
 
 def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
@@ -189,14 +212,14 @@ def unpack_weight_codes_t(pw: PackedWeight):
     return codes
 
 
-def quant_act_t(X):
+def quant_act_t(X, act_bits: int = 8):
     torch = _torch()
     assert X.is_cuda and X.is_contiguous() and X.dim() == 2
     M, K = X.shape
     qx = torch.empty((M, K), dtype=torch.int8, device=X.device)
     sx = torch.empty(M, dtype=torch.float32, device=X.device)
-    _check(qc_quant_act(X.data_ptr(), _xdt(X), M, K, qx.data_ptr(), sx.data_ptr(), _stream()),
-           "qc_quant_act")
+    _check(qc_quant_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, qx.data_ptr(), sx.data_ptr(),
+                             _stream()), "qc_quant_act_bits")
     return qx, sx
 
 
@@ -208,7 +231,8 @@ def qlinear_workspace_t(M: int, K: int, N: int, device="cuda"):
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=None, Y=None):
+def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=None, Y=None,
+              act_bits: int = 8):
     torch = _torch()
     assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == pw.K
     M, K = X.shape
@@ -217,9 +241,11 @@ def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=
     if Y is None:
         ydtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[out]
         Y = torch.empty((M, pw.N), dtype=ydtype, device=X.device)
-    _check(qc_qlinear(X.data_ptr(), _xdt(X), M, K, pw.blob.data_ptr(), pw.scale.data_ptr(), pw.bits,
-                      pw.N, None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
-                      OUT[out], workspace.data_ptr(), workspace.numel(), _stream()), "qc_qlinear")
+    _check(qc_qlinear_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, pw.blob.data_ptr(),
+                               pw.scale.data_ptr(), pw.bits, pw.N,
+                               None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
+                               OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
+           "qc_qlinear_act_bits")
     return Y
 
 

@@ -26,28 +26,46 @@ extern "C" size_t qc_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     return act_workspace(M, K).total_bytes;
 }
 
-extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
-                                  float *x_scale, void *stream) {
+namespace {
+bool act_bits_ok(int b) { return b == 8 || b == 6 || b == 4; }
+}  // namespace
+
+extern "C" qc_status qc_quant_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                       int act_bits, int8_t *qx, float *x_scale, void *stream) {
     if (!X || !qx || !x_scale || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
     if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
     if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
     if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, (hipStream_t)stream);
+    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, act_bits,
+                                    (hipStream_t)stream);
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }
 
-extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                      void *workspace, size_t workspace_bytes, void *stream) {
+extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
+                                  float *x_scale, void *stream) {
+    return qc_quant_act_bits(X, xdt, M, K, 8, qx, x_scale, stream);
+}
+
+extern "C" qc_status qc_qlinear_quant_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                           int act_bits, void *workspace, size_t workspace_bytes,
+                                           void *stream) {
     if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
     if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
     if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
     if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     const ActWorkspace ws = act_workspace(M, K);
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
     uint8_t *base = (uint8_t *)workspace;
     hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
-                                    (float *)base, (hipStream_t)stream);
+                                    (float *)base, act_bits, (hipStream_t)stream);
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                      void *workspace, size_t workspace_bytes, void *stream) {
+    return qc_qlinear_quant_bits(X, xdt, M, K, 8, workspace, workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
@@ -72,10 +90,11 @@ extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_byt
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }
 
-extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                const void *packed, const float *w_scale, int bits, int64_t N,
-                                const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
-                                void *workspace, size_t workspace_bytes, void *stream) {
+extern "C" qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                         int act_bits, const void *packed, const float *w_scale,
+                                         int bits, int64_t N, const float *bias, qc_epilogue epi,
+                                         void *Y, qc_out ydt, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
     // every argument is checked before the first launch, so a failed call has no side effect
     if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
         return QC_ERR_INVALID_ARG;
@@ -85,13 +104,22 @@ extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t 
     if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
         !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
         return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
     if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
     if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     const ActWorkspace ws = act_workspace(M, K);
     if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    qc_status st = qc_qlinear_quant(X, xdt, M, K, workspace, workspace_bytes, stream);
+    qc_status st = qc_qlinear_quant_bits(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream);
     if (st != QC_OK) return st;
     return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
                            ydt, stream);
+}
+
+extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                const void *packed, const float *w_scale, int bits, int64_t N,
+                                const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    return qc_qlinear_act_bits(X, xdt, M, K, 8, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                               workspace, workspace_bytes, stream);
 }

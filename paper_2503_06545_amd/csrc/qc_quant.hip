@@ -62,10 +62,10 @@ struct Unit<uint16_t> {  // bf16 bit patterns
     }
 };
 
-// code = clamp(rne(x / s), -127, 127): true IEEE division, then round half to even.
-__device__ inline int quant_code(float x, float s) {
+// code = clamp(rne(x / s), -qmax, qmax): true IEEE division, then round half to even.
+__device__ inline int quant_code(float x, float s, float qmax) {
     float r = rintf(x / s);
-    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    r = fminf(fmaxf(r, -qmax), qmax);
     return (int)r;
 }
 
@@ -77,21 +77,21 @@ __device__ inline float quotient(float x, float s, float r) {
     return q;
 }
 
-// Four quotients -> four int8 codes in one dword.  Clamping to [-127, 127] before rounding
+// Four quotients -> four int8 codes in one dword.  Clamping to [-qmax, qmax] before rounding
 // equals rounding then clamping; adding 1.5 * 2^23 rounds to an integer (ties to even) and
 // leaves its two's complement low byte in the low byte of the float.
-__device__ inline uint32_t codes4(float q0, float q1, float q2, float q3) {
+__device__ inline uint32_t codes4(float q0, float q1, float q2, float q3, float qmax) {
     const float magic = 12582912.0f;
-    const uint32_t y0 = __float_as_uint(__builtin_amdgcn_fmed3f(q0, -127.0f, 127.0f) + magic);
-    const uint32_t y1 = __float_as_uint(__builtin_amdgcn_fmed3f(q1, -127.0f, 127.0f) + magic);
-    const uint32_t y2 = __float_as_uint(__builtin_amdgcn_fmed3f(q2, -127.0f, 127.0f) + magic);
-    const uint32_t y3 = __float_as_uint(__builtin_amdgcn_fmed3f(q3, -127.0f, 127.0f) + magic);
+    const uint32_t y0 = __float_as_uint(__builtin_amdgcn_fmed3f(q0, -qmax, qmax) + magic);
+    const uint32_t y1 = __float_as_uint(__builtin_amdgcn_fmed3f(q1, -qmax, qmax) + magic);
+    const uint32_t y2 = __float_as_uint(__builtin_amdgcn_fmed3f(q2, -qmax, qmax) + magic);
+    const uint32_t y3 = __float_as_uint(__builtin_amdgcn_fmed3f(q3, -qmax, qmax) + magic);
     const uint32_t lo = __builtin_amdgcn_perm(y1, y0, 0x0c0c0400u);  // [y0.b0, y1.b0, 0, 0]
     const uint32_t hi = __builtin_amdgcn_perm(y3, y2, 0x04000c0cu);  // [0, 0, y2.b0, y3.b0]
     return lo | hi;
 }
 
-__device__ inline float scale_of(float absmax) { return fmaxf(absmax, kAbsmaxFloor) / 127.0f; }
+__device__ inline float scale_of(float absmax, float qmax) { return fmaxf(absmax, kAbsmaxFloor) / qmax; }
 
 // 8 lanes share a row and a wavefront holds 8 rows x 1152 columns (72 units of 16, 9 per lane)
 // in registers, so that every 16 B store of the fragment layout completes a 128 B line (8 rows
@@ -106,7 +106,7 @@ constexpr int kMaxSlices = 8;
 template <typename XT>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
-    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale) {
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax) {
     __shared__ float slice_max[kMaxSlices][kRowsPerBlock];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6, slices = blockDim.x >> 6;
     const int sub = lane % kLanesPerRow, row_in_block = lane / kLanesPerRow;
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
         for (int sl = 0; sl < slices; ++sl) a = fmaxf(a, slice_max[sl][row_in_block]);
     }
 
-    const float s = scale_of(a);
+    const float s = scale_of(a, qmax);
     const float r = 1.0f / s;  // correctly rounded
     if (live && sub == 0 && slice == 0) x_scale[row] = s;
     if (!live) return;
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
 #pragma unroll
         for (int d = 0; d < 4; ++d)
             w[d] = codes4(quotient(u[i].get(4 * d + 0), s, r), quotient(u[i].get(4 * d + 1), s, r),
-                          quotient(u[i].get(4 * d + 2), s, r), quotient(u[i].get(4 * d + 3), s, r));
+                          quotient(u[i].get(4 * d + 2), s, r), quotient(u[i].get(4 * d + 3), s, r), qmax);
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
         if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
         // unit ui covers k = 16 ui ..: fragment ui / 2, k half ui % 2 (see frag_offset)
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
 template <typename XT>
 __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
-    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale) {
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * (kGenericThreads / 64) + (threadIdx.x >> 6);
     if (row >= M) return;
@@ -179,10 +179,10 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
     for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(widen(xrow[k])));
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
-    const float s = scale_of(a);
+    const float s = scale_of(a, qmax);
     if (lane == 0) x_scale[row] = s;
     for (int64_t k = lane; k < K; k += 64) {
-        const int8_t c = (int8_t)quant_code(widen(xrow[k]), s);
+        const int8_t c = (int8_t)quant_code(widen(xrow[k]), s, qmax);
         if (qx) qx[row * K + k] = c;
         if (qx_tiled) qx_tiled[frag_offset(row, k, KF)] = (uint8_t)c;
     }
@@ -190,30 +190,33 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
 
 template <typename XT>
 hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
-                        int64_t KF, float *x_scale, hipStream_t stream) {
+                        int64_t KF, float *x_scale, float qmax, hipStream_t stream) {
     const int64_t units = K / kUnit;
     const int64_t slices = (units + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const bool vec = (K % kUnit == 0) && slices <= kMaxSlices;
     if (!vec) {
         const int64_t blocks = (M + 3) / 4;
         quant_rows_generic_kernel<XT><<<dim3((unsigned)blocks), dim3(kGenericThreads), 0, stream>>>(
-            X, M, K, qx, qx_tiled, KF, x_scale);
+            X, M, K, qx, qx_tiled, KF, x_scale, qmax);
         return hipGetLastError();
     }
     const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
     quant_rows_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
-        X, M, K, qx, qx_tiled, KF, x_scale);
+        X, M, K, qx, qx_tiled, KF, x_scale, qmax);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx_rowmajor,
-                            uint8_t *qx_tiled, int64_t KF, float *x_scale, hipStream_t stream) {
+                            uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
+                            hipStream_t stream) {
+    const float qmax = (float)((1 << (act_bits - 1)) - 1);  // 127, 31 or 7 in an int8 container
     if (xdt == QC_BF16)
         return launch_typed<uint16_t>((const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale,
-                                      stream);
-    return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, stream);
+                                      qmax, stream);
+    return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, qmax,
+                               stream);
 }
 
 }  // namespace qc

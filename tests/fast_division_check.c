@@ -19,13 +19,15 @@ static float fast_quotient(float x, float s, float r) {
     q = fmaf(fmaf(-s, q, x), r, q);
     return q;
 }
-static float code_of(float q) { return fminf(fmaxf(rintf(q), -127.f), 127.f); }
+static float qmax = 127.f;
+static float code_of(float q) { return fminf(fmaxf(rintf(q), -qmax), qmax); }
 
 static uint64_t state = 88172645463325252ULL;
 static uint64_t next(void) { state ^= state << 13; state ^= state >> 7; state ^= state << 17; return state; }
 
 int main(int argc, char **argv) {
     long scales = argc > 1 ? atol(argv[1]) : 400, randoms = argc > 2 ? atol(argv[2]) : 20000000;
+    if (argc > 3) qmax = (float)atof(argv[3]);
     long pairs = 0, bad_q = 0, bad_code = 0;
     for (long si = 0; si < scales; ++si) {
         uint32_t ab = (uint32_t)(next() & 0x7fffffff);
@@ -33,7 +35,7 @@ int main(int argc, char **argv) {
         memcpy(&a, &ab, 4);
         if (!(a > 0x1p-60f && a < 0x1p100f)) continue;
         if (si % 2) { ab &= 0xffff0000u; memcpy(&a, &ab, 4); }
-        float s = a / 127.0f, r = 1.0f / s;
+        float s = a / qmax, r = 1.0f / s;
         for (uint32_t hb = 0; hb < 65536; ++hb) {
             uint32_t u = hb << 16;
             float x;
@@ -50,11 +52,11 @@ int main(int argc, char **argv) {
         float a, x;
         memcpy(&a, &ab, 4);
         if (!(a > 0x1p-60f && a < 0x1p100f)) continue;
-        float s = a / 127.0f, r = 1.0f / s;
+        float s = a / qmax, r = 1.0f / s;
         if (it & 1) {
             x = a * ((float)(next() & 0xffffff) / 8388608.0f - 1.0f);
         } else { /* a half-integer multiple of s, nudged by a few ulps */
-            float k = (float)((int)(next() % 255) - 127) + 0.5f;
+            float k = (float)((int)(next() % (2 * (int)qmax + 1)) - (int)qmax) + 0.5f;
             uint32_t xb;
             x = k * s;
             memcpy(&xb, &x, 4);

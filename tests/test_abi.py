@@ -55,6 +55,12 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_quant_act(A, 7, 4, 16, A, A) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_quant_act(A + 2, qc.QC_BF16, 4, 16, A, A) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_quant_act(A, qc.QC_BF16, 4, qc.QC_MAX_K + 1, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_bits(A, qc.QC_BF16, 4, 16, 5, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_bits(None, qc.QC_BF16, 4, 16, 6, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_qlinear_quant_bits(A, qc.QC_BF16, 4, 16, 3, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_qlinear_quant_bits(A, qc.QC_BF16, 4, 16, 6, A, 16) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_qlinear_act_bits(A, qc.QC_BF16, 4, 16, 7, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
+                                  qc.QC_OUT_BF16, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
     assert qc.qc_pack_weight(A, 8, 15, 4, A, A) == qc.QC_ERR_UNSUPPORTED
     assert qc.qc_pack_weight(A, 8, 16, 3, A, A) == qc.QC_ERR_UNSUPPORTED
     assert qc.qc_pack_weight(A, 8, 16, 8, A + 16, A) == qc.QC_ERR_INVALID_ARG

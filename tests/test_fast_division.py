@@ -15,7 +15,10 @@ def test_reciprocal_plus_two_fma_corrections_equals_ieee_division():
         exe = os.path.join(tmp, "fast_division_check")
         subprocess.run(["gcc", "-O2", "-mfma", "-ffp-contract=off",
                         os.path.join(HERE, "fast_division_check.c"), "-o", exe, "-lm"], check=True)
-        out = subprocess.run([exe, "400", "20000000"], check=True, capture_output=True, text=True)
-    pairs, bad_quotients, bad_codes = (int(v) for v in out.stdout.split())
-    assert pairs > 15_000_000
-    assert bad_quotients == 0 and bad_codes == 0
+        for qmax, scales, randoms in (("127", "400", "20000000"), ("31", "150", "6000000"),
+                                      ("7", "150", "6000000")):
+            out = subprocess.run([exe, scales, randoms, qmax], check=True, capture_output=True,
+                                 text=True)
+            pairs, bad_quotients, bad_codes = (int(v) for v in out.stdout.split())
+            assert pairs > 5_000_000
+            assert bad_quotients == 0 and bad_codes == 0, (qmax, bad_quotients, bad_codes)

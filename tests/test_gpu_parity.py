@@ -85,6 +85,20 @@ def test_quant_act_tiny_config_and_ties():
     assert torch.equal(qx[1], -qx[0])
 
 
+@pytest.mark.parametrize("act_bits", [6, 4])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K", [(256, 1152), (77, 4608), (9, 1000)])
+def test_quant_act_lower_bit_widths(act_bits, dtype, M, K):
+    rng = np.random.default_rng(M + K + act_bits)
+    x = random_x(rng, M, K, dtype)
+    q_ref, s_ref = oracle.quant_act(x, act_bits)
+    qx, sx = qc.quant_act_t(dev(x), act_bits)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), s_ref)
+    assert np.array_equal(qx.cpu().numpy(), q_ref)
+    assert int(qx.abs().max()) == (1 << (act_bits - 1)) - 1
+
+
 # ------------------------------------------------------------------ qc_pack_weight
 
 @pytest.mark.parametrize("bits", [8, 4])
@@ -119,21 +133,21 @@ def test_pack_int4_all_nibbles_all_positions():
 
 # ------------------------------------------------------------------ qc_qlinear
 
-def run_linear_case(x, W, b, bits, epi, out, check_acc=True):
+def run_linear_case(x, W, b, bits, epi, out, check_acc=True, act_bits=8):
     M, K = x.shape
     N = W.shape[0]
     qw_ref, sw_ref = oracle.quant_weight(W, bits)
-    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi])
+    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi], act_bits)
     xd, pw = dev(x), qc.pack_weight_t(dev(W), bits)
     bd = None if b is None else dev(b)
     ws = qc.qlinear_workspace_t(M, K, N)
-    y = qc.qlinear_t(xd, pw, bd, epi, out, workspace=ws)
+    y = qc.qlinear_t(xd, pw, bd, epi, out, workspace=ws, act_bits=act_bits)
     qx, sx = qc.debug_workspace_act_t(ws, M, K)
     torch.cuda.synchronize()
     assert bits_equal(sx.cpu().numpy(), ref["sx"]), "activation scales differ"
     assert np.array_equal(qx.cpu().numpy(), ref["qx"]), "activation codes differ"
     if check_acc:
-        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws, act_bits=act_bits)
         torch.cuda.synchronize()
         assert np.array_equal(acc.cpu().numpy(), ref["acc"]), "int32 accumulators differ"
     y_ref = ref["y"]
@@ -160,6 +174,18 @@ def test_qlinear_variants(bits, epi, out):
     W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
     b = (rng.standard_normal(N) * 0.01).astype(np.float32)
     run_linear_case(x, W, b, bits, epi, out)
+
+
+@pytest.mark.parametrize("bits,act_bits", [(4, 6), (8, 6), (4, 4)])
+def test_qlinear_lower_activation_bit_widths(bits, act_bits):
+    """The paper's W4A6 operating point and its neighbours: same GEMM, coarser activation codes."""
+    rng = np.random.default_rng(bits * 10 + act_bits)
+    M, K, N = 640, 1152, 256
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_linear_case(x, W, b, bits, "gelu_tanh", "bf16", act_bits=act_bits)
+    run_linear_case(x, W, b, bits, "none", "f32", act_bits=act_bits)
 
 
 @pytest.mark.parametrize("bits", [8, 4])

@@ -73,7 +73,7 @@ def test_round_helper_matches_numpy_cast():
 
 # ------------------------------------------------------------------ quantizer
 
-@pytest.mark.parametrize("qmax", [127, 7])
+@pytest.mark.parametrize("qmax", [127, 31, 7])
 def test_quantizer_against_exact_rational_brute_force(qmax):
     rng = np.random.default_rng(0)
     X = rng.standard_normal((6, 8)).astype(np.float32)
@@ -100,7 +100,7 @@ def test_scale_is_symmetrised_range_over_levels(bits):
         assert float(s[n]) == expect
 
 
-@pytest.mark.parametrize("qmax", [127, 7])
+@pytest.mark.parametrize("qmax", [127, 31, 7])
 def test_fp64_brute_force_agrees_away_from_ties(qmax):
     rng = np.random.default_rng(5)
     X = rng.standard_normal((64, 96)).astype(np.float32)
@@ -113,7 +113,7 @@ def test_fp64_brute_force_agrees_away_from_ties(qmax):
     assert np.array_equal(q[~near_tie], ref[~near_tie].astype(np.int8))
 
 
-@pytest.mark.parametrize("qmax", [127, 7])
+@pytest.mark.parametrize("qmax", [127, 31, 7])
 def test_half_step_invariant_and_full_range(qmax):
     rng = np.random.default_rng(7)
     X = rng.standard_normal((128, 1152)).astype(np.float32)
@@ -160,6 +160,26 @@ def test_odd_symmetry_and_power_of_two_equivariance():
         q2, s2 = oracle.quant_act(X * np.float32(2.0 ** j))
         assert np.array_equal(q2, q)
         assert np.array_equal(s2, s * np.float32(2.0 ** j))
+
+
+def test_activation_bit_widths_share_one_quantizer():
+    """act_bits 8 / 6 / 4 are the same quantizer with qmax 127 / 31 / 7 in an int8 container."""
+    rng = np.random.default_rng(15)
+    X = rng.standard_normal((8, 64)).astype(np.float32)
+    for bits, qm in ((8, 127), (6, 31), (4, 7)):
+        q, s = oracle.quant_act(X, bits)
+        q2, s2 = oracle._quant_rows(X, qm)
+        assert np.array_equal(q, q2) and np.array_equal(s, s2)
+        assert np.abs(q.astype(np.int32)).max() == qm
+        ints = rng.integers(-qm, qm + 1, size=(4, 32)).astype(np.float32)
+        ints[:, 0] = qm
+        qi, si = oracle.quant_act(ints, bits)
+        assert np.all(si == 1.0) and np.array_equal(qi, ints.astype(np.int8))
+    W = (rng.standard_normal((6, 64)) * 0.02).astype(np.float32)
+    qw, sw = oracle.quant_weight(W, 4)
+    out = oracle.qlinear(X, qw, sw, None, oracle.EPI_NONE, act_bits=6)
+    q6, s6 = oracle.quant_act(X, 6)
+    assert np.array_equal(out["qx"], q6) and np.array_equal(out["acc"], oracle.gemm_i32(q6, qw))
 
 
 def test_zero_and_tiny_rows_use_the_absmax_floor():
