@@ -172,6 +172,19 @@ qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K, in
 qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float *out3,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- cosine similarity of the features of consecutive layers -----------------------------
+ * Section 3.3 SRAP, Eq. (9): S = <a, b> / (||a|| ||b||), the score the layer-pruning rule of
+ * Eq. (10) thresholds.  (The cumulative variation of Eq. (11) is a sum of qc_latent_delta's
+ * first output over the cached steps.)
+ *   a, b       device, [n] of `dt` (float or bf16)
+ *   out4       device, float [4]: { <a,b>, <a,a>, <b,b>, S };  S = 0 if either norm is 0
+ *   workspace  device, >= qc_layer_similarity_workspace_bytes(n) bytes, 256-byte aligned,
+ *              contents irrelevant on entry
+ * Deterministic like qc_latent_delta.  Errors: INVALID_ARG, WORKSPACE, DEVICE. */
+size_t qc_layer_similarity_workspace_bytes(int64_t n);
+qc_status qc_layer_similarity(const void *a, const void *b, qc_dtype dt, int64_t n, float *out4,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

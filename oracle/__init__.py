@@ -14,6 +14,7 @@ Paper passages each function follows (arxiv 2503.06545):
   gemm_i32, epilogue,       Section 4.1 "Hardware Implementation" (low-bit GEMM with
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
+  layer_similarity          Section 3.3 SRAP, Eq. (9)
 """
 from __future__ import annotations
 
@@ -60,6 +61,8 @@ def _L():
         lib.orc_round_to_bf16.argtypes = [vp, i64, vp]
         lib.orc_qlinear.argtypes = [vp, i32, i64, i64, i32, vp, vp, i64, vp, i32, vp, vp, vp, vp]
         lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
+        lib.orc_layer_similarity.argtypes = [vp, vp, i32, i64, vp]
+        lib.orc_layer_similarity.restype = None
         for name in ("orc_set_num_threads", "orc_quant_rows_f32", "orc_quant_rows_bf16",
                      "orc_pack_int4", "orc_unpack_int4", "orc_gemm_i32", "orc_gemm_i64",
                      "orc_epilogue_f64", "orc_round_to_f32", "orc_round_to_bf16", "orc_qlinear",
@@ -214,4 +217,15 @@ def latent_delta(cur, prev):
     assert cur.size == prev.size
     out = np.empty(3, np.float64)
     _L().orc_latent_delta(_p(cur), _p(prev), cur.size, _p(out))
+    return out
+
+
+def layer_similarity(a, b):
+    """(<a,b>, <a,a>, <b,b>, cosine) in float64; a, b float32 or uint16 (bf16 bits)."""
+    is_bf16 = a.dtype == np.uint16
+    dt = np.uint16 if is_bf16 else np.float32
+    a, b = _c(a, dt).ravel(), _c(b, dt).ravel()
+    assert a.size == b.size
+    out = np.empty(4, np.float64)
+    _L().orc_layer_similarity(_p(a), _p(b), int(is_bf16), a.size, _p(out))
     return out

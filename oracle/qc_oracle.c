@@ -236,3 +236,30 @@ void orc_latent_delta(const float *cur, const float *prev, int64_t n, double out
     if (den > 0.0) out[2] = num / den;
     else out[2] = num > 0.0 ? INFINITY : 0.0;
 }
+
+/*
+ * Cosine similarity of the features of two consecutive layers (Section 3.3 SRAP, Eq. (9)):
+ *   S = <a, b> / (||a|| ||b||), sequential binary64 sums; S = 0 if either norm is 0.
+ * out: { <a,b>, <a,a>, <b,b>, S }.  a_is_bf16 selects how both inputs are read.
+ */
+void orc_layer_similarity(const void *a, const void *b, int is_bf16, int64_t n, double out[4]) {
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        double x, y;
+        if (is_bf16) {
+            x = (double)bf16_bits_to_f32(((const uint16_t *)a)[i]);
+            y = (double)bf16_bits_to_f32(((const uint16_t *)b)[i]);
+        } else {
+            x = (double)((const float *)a)[i];
+            y = (double)((const float *)b)[i];
+        }
+        ab += x * y;
+        aa += x * x;
+        bb += y * y;
+    }
+    out[0] = ab;
+    out[1] = aa;
+    out[2] = bb;
+    double denom = sqrt(aa) * sqrt(bb);
+    out[3] = denom > 0.0 ? ab / denom : 0.0;
+}

@@ -23,7 +23,8 @@ EXPORTS = (
     "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",
     "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
     "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_quant_act_bits",
-    "qc_qlinear_quant_bits", "qc_qlinear_act_bits", "qc_debug_workspace_act", "qc_latent_delta",
+    "qc_qlinear_quant_bits", "qc_qlinear_act_bits", "qc_layer_similarity_workspace_bytes",
+    "qc_layer_similarity", "qc_debug_workspace_act", "qc_latent_delta",
 )
 
 
@@ -73,6 +74,10 @@ def lib() -> ctypes.CDLL:
         L.qc_qlinear_act_bits.restype = i32
         L.qc_qlinear_act_bits.argtypes = [vp, i32, i64, i64, i32, vp, vp, i32, i64, vp, i32, vp, i32,
                                           vp, sz, vp]
+        L.qc_layer_similarity_workspace_bytes.restype = sz
+        L.qc_layer_similarity_workspace_bytes.argtypes = [i64]
+        L.qc_layer_similarity.restype = i32
+        L.qc_layer_similarity.argtypes = [vp, vp, i32, i64, vp, vp, sz, vp]
         L.qc_debug_workspace_act.restype = i32
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
@@ -144,6 +149,14 @@ def qc_qlinear_act_bits(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias, 
                         workspace, workspace_bytes, stream=0) -> int:
     return int(lib().qc_qlinear_act_bits(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias,
                                          epi, Y, ydt, workspace, workspace_bytes, stream))
+
+
+def qc_layer_similarity_workspace_bytes(n: int) -> int:
+    return int(lib().qc_layer_similarity_workspace_bytes(n))
+
+
+def qc_layer_similarity(a, b, dt, n, out4, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_layer_similarity(a, b, dt, n, out4, workspace, workspace_bytes, stream))
 
 
 def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
@@ -275,3 +288,19 @@ def latent_delta_t(cur, prev, workspace=None, out3=None):
     _check(qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n, out3.data_ptr(), workspace.data_ptr(),
                            workspace.numel(), _stream()), "qc_latent_delta")
     return out3
+
+
+def layer_similarity_t(a, b, workspace=None, out4=None):
+    torch = _torch()
+    assert a.is_cuda and a.is_contiguous() and b.is_contiguous()
+    assert a.shape == b.shape and a.dtype == b.dtype
+    n = a.numel()
+    if workspace is None:
+        workspace = torch.empty(qc_layer_similarity_workspace_bytes(n), dtype=torch.uint8,
+                                device=a.device)
+    if out4 is None:
+        out4 = torch.empty(4, dtype=torch.float32, device=a.device)
+    _check(qc_layer_similarity(a.data_ptr(), b.data_ptr(), _xdt(a), n, out4.data_ptr(),
+                               workspace.data_ptr(), workspace.numel(), _stream()),
+           "qc_layer_similarity")
+    return out4

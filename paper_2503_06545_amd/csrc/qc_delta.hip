@@ -99,6 +99,111 @@ __global__ __launch_bounds__(kThreads) void latent_delta_final_kernel(
     }
 }
 
+// ---- cosine similarity of two feature tensors (Section 3.3 SRAP, Eq. (9)) -------------------
+// Same scheme with three running sums: <a, b>, <a, a>, <b, b>.
+
+// 8 consecutive elements of a float or bf16 tensor, widened to float
+template <typename T>
+struct Oct;
+template <>
+struct Oct<float> {
+    float4 lo, hi;
+    __device__ void load(const float *p) {
+        lo = reinterpret_cast<const float4 *>(p)[0];
+        hi = reinterpret_cast<const float4 *>(p)[1];
+    }
+    __device__ float get(int i) const {
+        const float4 &f = i < 4 ? lo : hi;
+        switch (i & 3) { case 0: return f.x; case 1: return f.y; case 2: return f.z; default: return f.w; }
+    }
+};
+template <>
+struct Oct<uint16_t> {  // bf16 bit patterns
+    uint4 v;
+    __device__ void load(const uint16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ float get(int i) const {
+        uint32_t w;
+        switch (i >> 1) { case 0: w = v.x; break; case 1: w = v.y; break; case 2: w = v.z; break; default: w = v.w; }
+        return __uint_as_float((i & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
+    const T *__restrict__ a, const T *__restrict__ b, int64_t n, double *__restrict__ partials) {
+    __shared__ double sh[3 * (kThreads / 64)];
+    const int64_t n8 = n / 8;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n8; i += 2 * stride) {
+        Oct<T> x[2], y[2];
+        const bool second = i + stride < n8;
+        x[0].load(a + 8 * i);
+        y[0].load(b + 8 * i);
+        if (second) { x[1].load(a + 8 * (i + stride)); y[1].load(b + 8 * (i + stride)); }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (u == 1 && !second) break;
+            float pab[2] = {0.f, 0.f}, paa[2] = {0.f, 0.f}, pbb[2] = {0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {  // two 4-term binary32 sums each
+                const float xv = x[u].get(e), yv = y[u].get(e);
+                pab[e >> 2] += xv * yv;
+                paa[e >> 2] += xv * xv;
+                pbb[e >> 2] += yv * yv;
+            }
+            ab += (double)pab[0] + (double)pab[1];
+            aa += (double)paa[0] + (double)paa[1];
+            bb += (double)pbb[0] + (double)pbb[1];
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (int)(n - n8 * 8)) {  // up to 7 trailing elements
+        const int64_t j = n8 * 8 + threadIdx.x;
+        float xv, yv;
+        if constexpr (sizeof(T) == 2) {
+            xv = __uint_as_float((uint32_t)a[j] << 16);
+            yv = __uint_as_float((uint32_t)b[j] << 16);
+        } else {
+            xv = a[j];
+            yv = b[j];
+        }
+        ab += (double)(xv * yv);
+        aa += (double)(xv * xv);
+        bb += (double)(yv * yv);
+    }
+    ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sh[3 * wave] = ab; sh[3 * wave + 1] = aa; sh[3 * wave + 2] = bb; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) { sh[0] += sh[3 * w]; sh[1] += sh[3 * w + 1]; sh[2] += sh[3 * w + 2]; }
+        partials[3 * blockIdx.x] = sh[0];
+        partials[3 * blockIdx.x + 1] = sh[1];
+        partials[3 * blockIdx.x + 2] = sh[2];
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void similarity_final_kernel(
+    const double *__restrict__ partials, int count, float *__restrict__ out4) {
+    __shared__ double sh[3 * (kThreads / 64)];
+    double ab = 0.0, aa = 0.0, bb = 0.0;
+    for (int b = threadIdx.x; b < count; b += kThreads) {
+        ab += partials[3 * b]; aa += partials[3 * b + 1]; bb += partials[3 * b + 2];
+    }
+    ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sh[3 * wave] = ab; sh[3 * wave + 1] = aa; sh[3 * wave + 2] = bb; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) { sh[0] += sh[3 * w]; sh[1] += sh[3 * w + 1]; sh[2] += sh[3 * w + 2]; }
+        const double denom = sqrt(sh[1]) * sqrt(sh[2]);
+        out4[0] = (float)sh[0];
+        out4[1] = (float)sh[1];
+        out4[2] = (float)sh[2];
+        out4[3] = denom > 0.0 ? (float)(sh[0] / denom) : 0.0f;
+    }
+}
+
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 }  // namespace
@@ -127,5 +232,33 @@ extern "C" qc_status qc_latent_delta(const float *cur, const float *prev, int64_
     if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
     latent_delta_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(
         partials, (int)blocks, out3);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" size_t qc_layer_similarity_workspace_bytes(int64_t n) {
+    if (n < 1) return 0;
+    return (size_t)kMaxBlocks * 3 * sizeof(double);
+}
+
+extern "C" qc_status qc_layer_similarity(const void *a, const void *b, qc_dtype dt, int64_t n,
+                                         float *out4, void *workspace, size_t workspace_bytes,
+                                         void *stream) {
+    if (!a || !b || !out4 || !workspace || n < 1) return QC_ERR_INVALID_ARG;
+    if (dt != QC_F32 && dt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out4, 4) || !aligned(workspace, 256))
+        return QC_ERR_INVALID_ARG;
+    if (workspace_bytes < qc_layer_similarity_workspace_bytes(n)) return QC_ERR_WORKSPACE;
+    int64_t blocks = (n / 8 + (int64_t)kThreads * 2 - 1) / ((int64_t)kThreads * 2);
+    if (blocks < 1) blocks = 1;
+    if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+    double *partials = (double *)workspace;
+    if (dt == QC_BF16)
+        similarity_partial_kernel<uint16_t><<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+            (const uint16_t *)a, (const uint16_t *)b, n, partials);
+    else
+        similarity_partial_kernel<float><<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+            (const float *)a, (const float *)b, n, partials);
+    if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
+    similarity_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(partials, (int)blocks, out4);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }

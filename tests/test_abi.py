@@ -81,6 +81,10 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_latent_delta(A, A, 0, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_latent_delta(A, A + 4, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_latent_delta(A, A, 8, A, A, 8) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_layer_similarity(A, None, qc.QC_F32, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_layer_similarity(A, A, 5, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_layer_similarity(A, A, qc.QC_BF16, 8, A, A, 8) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_layer_similarity_workspace_bytes(100) == 256 * 24
 
 
 def test_missing_library_is_a_loud_error(monkeypatch):

@@ -323,3 +323,28 @@ def test_latent_delta_closed_forms_and_determinism():
     assert 0.009 < first[2] < 0.011
     for _ in range(10):
         assert bits_equal(qc.latent_delta_t(c, p, workspace=ws).cpu().numpy(), first)
+
+
+# ------------------------------------------------------------------ qc_layer_similarity
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 7, 8, 9, 4096, 100003, 65536 * 1152])
+def test_layer_similarity_matches_oracle(dtype, n):
+    cur, prev = synth.latent_pair(seed=n % 89, n=n, delta=0.5)
+    if dtype == "bf16":
+        cur, prev = synth.to_bf16_bits(cur), synth.to_bf16_bits(prev)
+    ref = oracle.layer_similarity(cur, prev)
+    got = qc.layer_similarity_t(dev(cur), dev(prev)).cpu().numpy().astype(np.float64)
+    norm = math.sqrt(ref[1] * ref[2])
+    assert abs(got[0] - ref[0]) <= 1e-6 * norm + 1e-30
+    assert abs(got[1] - ref[1]) <= 1e-6 * ref[1] and abs(got[2] - ref[2]) <= 1e-6 * ref[2]
+    assert abs(got[3] - ref[3]) <= 2e-6
+    again = qc.layer_similarity_t(dev(cur), dev(prev)).cpu().numpy()
+    assert bits_equal(again, got.astype(np.float32))
+
+
+def test_layer_similarity_closed_forms():
+    a = torch.randn(1 << 20, device="cuda")
+    assert abs(qc.layer_similarity_t(a, a).cpu().tolist()[3] - 1.0) < 1e-6
+    assert abs(qc.layer_similarity_t(a, -a).cpu().tolist()[3] + 1.0) < 1e-6
+    assert qc.layer_similarity_t(a, torch.zeros_like(a)).cpu().tolist()[3] == 0.0

@@ -369,3 +369,38 @@ def test_latent_delta_against_compensated_sum():
     assert abs(num - rn) <= 1e-11 * rn and abs(den - rd) <= 1e-11 * rd
     assert abs(rel - rn / rd) <= 1e-11 * rel
     assert 0.008 < rel < 0.012
+
+
+# ------------------------------------------------------------------ layer similarity (Eq. (9))
+
+def test_layer_similarity_closed_forms():
+    rng = np.random.default_rng(53)
+    a = rng.standard_normal(4099).astype(np.float32)
+    dot, aa, bb, cos = oracle.layer_similarity(a, a)
+    assert abs(cos - 1.0) < 1e-15 and dot == aa == bb
+    assert abs(oracle.layer_similarity(a, -a)[3] + 1.0) < 1e-15
+    assert abs(oracle.layer_similarity(a, a * np.float32(4.0))[3] - 1.0) < 1e-15   # scale invariant
+    e0 = np.zeros(8, np.float32); e0[0] = 3
+    e1 = np.zeros(8, np.float32); e1[1] = -2
+    assert oracle.layer_similarity(e0, e1).tolist() == [0.0, 9.0, 4.0, 0.0]
+    assert oracle.layer_similarity(e0, np.zeros(8, np.float32))[3] == 0.0
+    # 45 degrees: (1, 0) against (1, 1)
+    u = np.array([1, 0], np.float32); v = np.array([1, 1], np.float32)
+    assert abs(oracle.layer_similarity(u, v)[3] - math.sqrt(0.5)) < 1e-15
+    # order of the arguments: <a,a> first, <b,b> second
+    assert oracle.layer_similarity(e0, v[:1].repeat(8))[1:3].tolist() == [9.0, 8.0]
+
+
+def test_layer_similarity_against_numpy_and_bf16_reading():
+    rng = np.random.default_rng(59)
+    a = rng.standard_normal(100003).astype(np.float32)
+    b = (a + 0.3 * rng.standard_normal(100003)).astype(np.float32)
+    got = oracle.layer_similarity(a, b)
+    a64, b64 = a.astype(np.float64), b.astype(np.float64)
+    ref = [math.fsum(a64 * b64), math.fsum(a64 * a64), math.fsum(b64 * b64)]
+    assert np.allclose(got[:3], ref, rtol=1e-12)
+    assert abs(got[3] - ref[0] / math.sqrt(ref[1] * ref[2])) < 1e-12 and abs(got[3]) <= 1.0
+    from paper_2503_06545_amd import synth
+    ab, bb = synth.to_bf16_bits(a), synth.to_bf16_bits(b)
+    widened = lambda x: (x.astype(np.uint32) << 16).view(np.float32)
+    assert np.array_equal(oracle.layer_similarity(ab, bb), oracle.layer_similarity(widened(ab), widened(bb)))
