@@ -15,6 +15,12 @@ Paper passages each function follows (arxiv 2503.06545):
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
   layer_similarity          Section 3.3 SRAP, Eq. (9)
+  frame_gradient,           Section 3.2 HLC, Eq. (5): the inter-frame gradient factor and the
+  divergence_score          score built from it and latent_delta's first sum
+  cumulative_variation      Section 3.3 SRAP, Eq. (11)
+  cache_interval,           the three-way threshold rules: Section 3.2 Eq. (6) and Eq. (8),
+  activation_bits,          Section 3.3 Eq. (10)
+  prune_probability
 """
 from __future__ import annotations
 
@@ -63,6 +69,10 @@ def _L():
         lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
         lib.orc_layer_similarity.argtypes = [vp, vp, i32, i64, vp]
         lib.orc_layer_similarity.restype = None
+        lib.orc_frame_gradient.argtypes = [vp, i32, i64, i64, vp]
+        lib.orc_frame_gradient.restype = None
+        lib.orc_cumulative_variation.argtypes = [vp, vp, i32, i64, vp]
+        lib.orc_cumulative_variation.restype = None
         for name in ("orc_set_num_threads", "orc_quant_rows_f32", "orc_quant_rows_bf16",
                      "orc_pack_int4", "orc_unpack_int4", "orc_gemm_i32", "orc_gemm_i64",
                      "orc_epilogue_f64", "orc_round_to_f32", "orc_round_to_bf16", "orc_qlinear",
@@ -229,3 +239,57 @@ def layer_similarity(a, b):
     out = np.empty(4, np.float64)
     _L().orc_layer_similarity(_p(a), _p(b), int(is_bf16), a.size, _p(out))
     return out
+
+
+def frame_gradient(m):
+    """m: float32 or uint16 (bf16 bits) [frames, inner] -> (sum of squared forward differences
+    along the frame axis, its square root) in float64."""
+    is_bf16 = m.dtype == np.uint16
+    m = _c(m, np.uint16 if is_bf16 else np.float32)
+    frames, inner = m.shape
+    out = np.empty(2, np.float64)
+    _L().orc_frame_gradient(_p(m), int(is_bf16), frames, inner, _p(out))
+    return out
+
+
+def cumulative_variation(cur, prevs):
+    """cur float32 [n], prevs float32 [count, n] -> float64 [count + 1]: each L1 distance, then
+    their sum V (Eq. (11))."""
+    cur = _c(cur, np.float32).ravel()
+    prevs = _c(prevs, np.float32).reshape(-1, cur.size)
+    out = np.empty(prevs.shape[0] + 1, np.float64)
+    _L().orc_cumulative_variation(_p(cur), _p(prevs), prevs.shape[0], cur.size, _p(out))
+    return out
+
+
+def divergence_score(l1_change: float, k: int, grad_norm: float) -> float:
+    """Eq. (5): the L1 change since the cached step, per step, times the gradient norm."""
+    return float(l1_change) / float(k) * float(grad_norm)
+
+
+def _three_way(value, low, high, below, between, above):
+    """below if value < low, between if low <= value < high, above if value >= high."""
+    if value < low:
+        return below
+    if value < high:
+        return between
+    return above
+
+
+def cache_interval(D, delta1, delta2, tau_max, tau_mid, tau_min):
+    """Eq. (6): steps until the next recomputation."""
+    return _three_way(D, delta1, delta2, tau_max, tau_mid, tau_min)
+
+
+def activation_bits(D, theta1, theta2, bit_max, bit_mid, bit_min):
+    """Eq. (8): activation bit-width of a timestep from its redundancy metric."""
+    return _three_way(D, theta1, theta2, bit_max, bit_mid, bit_min)
+
+
+def prune_probability(S, tau_low, tau_high, p_base):
+    """Eq. (10): 1 above tau_high, p_base on [tau_low, tau_high], 0 below tau_low."""
+    if S > tau_high:
+        return 1.0
+    if S < tau_low:
+        return 0.0
+    return float(p_base)

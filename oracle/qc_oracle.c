@@ -18,7 +18,14 @@
  *   - Section 4.1 "Hardware Implementation": the linear layer runs as a
  *     low-bit integer GEMM with the (de)quantization fused around it;
  *   - Section 3.2 HLC, Eq. (5): the L1 norm of the change of a latent between
- *     the current and the cached step.
+ *     the current and the cached step; its second factor, the norm of the
+ *     inter-frame gradient of the feature map, is named there and not defined.
+ *     orc_frame_gradient takes one reading of it (forward difference along the
+ *     frame axis, Euclidean norm).  The arithmetic of that reading is pinned by
+ *     the tests; that it is the authors' definition cannot be checked from the
+ *     paper: parity unpinned for this function in that sense;
+ *   - Section 3.3 SRAP, Eq. (9) (cosine similarity of consecutive layers) and
+ *     Eq. (11) (cumulative L1 variation over the previous steps).
  *
  * Arithmetic contract.  The steps marked [bit] are single IEEE-754 binary32
  * operations, round to nearest even, written one per statement so that no
@@ -262,4 +269,48 @@ void orc_layer_similarity(const void *a, const void *b, int is_bf16, int64_t n, 
     out[2] = bb;
     double denom = sqrt(aa) * sqrt(bb);
     out[3] = denom > 0.0 ? ab / denom : 0.0;
+}
+
+/*
+ * Inter-frame gradient of a feature map (Section 3.2 HLC, the second factor of Eq. (5)).
+ * The paper names the factor and does not define it; the reading taken here: m is laid out
+ * [frames, inner], the gradient is the forward difference along the frame axis,
+ * g[f, j] = m[f+1, j] - m[f, j] for f < frames-1, and the norm is the Euclidean norm over
+ * all of g.  out: { sum g^2, sqrt of it }.  One frame gives 0.
+ */
+void orc_frame_gradient(const void *m, int is_bf16, int64_t frames, int64_t inner, double out[2]) {
+    double ss = 0.0;
+    for (int64_t f = 0; f + 1 < frames; ++f)
+        for (int64_t j = 0; j < inner; ++j) {
+            double lo, hi;
+            if (is_bf16) {
+                lo = (double)bf16_bits_to_f32(((const uint16_t *)m)[f * inner + j]);
+                hi = (double)bf16_bits_to_f32(((const uint16_t *)m)[(f + 1) * inner + j]);
+            } else {
+                lo = (double)((const float *)m)[f * inner + j];
+                hi = (double)((const float *)m)[(f + 1) * inner + j];
+            }
+            ss += (hi - lo) * (hi - lo);
+        }
+    out[0] = ss;
+    out[1] = sqrt(ss);
+}
+
+/*
+ * Cumulative feature variation over the previous steps (Section 3.3 SRAP, Eq. (11)):
+ *   V = sum_i || p_t - p_{t-i} ||_1.   prevs holds the `count` earlier tensors back to back,
+ * [count, n]; the i = 0 term of the printed sum is identically zero and is not stored.
+ * out: the `count` L1 distances, then V.
+ */
+void orc_cumulative_variation(const float *cur, const float *prevs, int count, int64_t n,
+                              double *out) {
+    double total = 0.0;
+    for (int c = 0; c < count; ++c) {
+        double d = 0.0;
+        for (int64_t i = 0; i < n; ++i)
+            d += fabs((double)cur[i] - (double)prevs[(int64_t)c * n + i]);
+        out[c] = d;
+        total += d;
+    }
+    out[count] = total;
 }

@@ -404,3 +404,83 @@ def test_layer_similarity_against_numpy_and_bf16_reading():
     ab, bb = synth.to_bf16_bits(a), synth.to_bf16_bits(b)
     widened = lambda x: (x.astype(np.uint32) << 16).view(np.float32)
     assert np.array_equal(oracle.layer_similarity(ab, bb), oracle.layer_similarity(widened(ab), widened(bb)))
+
+
+# ------------------------------------------------- inter-frame gradient (Eq. (5), second factor)
+
+def test_frame_gradient_closed_forms():
+    rng = np.random.default_rng(61)
+    # a ramp in time: every forward difference is v, so the sum is (F - 1) |v|^2
+    v = rng.integers(-8, 8, size=37).astype(np.float32)
+    F = 6
+    ramp = np.arange(F, dtype=np.float32)[:, None] * v[None, :] + np.float32(5.0)
+    ss, norm = oracle.frame_gradient(ramp)
+    assert ss == (F - 1) * float((v.astype(np.float64) ** 2).sum()) and norm == math.sqrt(ss)
+    # constant in time, and a single frame: no motion
+    still = np.tile(rng.standard_normal(37).astype(np.float32), (4, 1))
+    assert oracle.frame_gradient(still).tolist() == [0.0, 0.0]
+    assert oracle.frame_gradient(still[:1]).tolist() == [0.0, 0.0]
+    # only neighbouring frames meet: one hot frame contributes twice (rise and fall), the
+    # first or last frame once
+    m = np.zeros((5, 3), np.float32)
+    m[2, 1] = 3
+    assert oracle.frame_gradient(m)[0] == 18.0
+    m[:] = 0
+    m[4, 0] = 3
+    assert oracle.frame_gradient(m)[0] == 9.0
+    # the difference runs along the first axis, not the second
+    t = np.array([[0, 10], [1, 11]], np.float32)
+    assert oracle.frame_gradient(t)[0] == 2.0 and oracle.frame_gradient(t.T.copy())[0] == 200.0
+
+
+def test_frame_gradient_against_numpy_and_bf16_reading():
+    rng = np.random.default_rng(67)
+    m = rng.standard_normal((9, 4001)).astype(np.float32)
+    ss, norm = oracle.frame_gradient(m)
+    ref = math.fsum((np.diff(m.astype(np.float64), axis=0) ** 2).ravel())
+    assert abs(ss - ref) <= 1e-12 * ref and abs(norm - math.sqrt(ref)) <= 1e-12 * norm
+    from paper_2503_06545_amd import synth
+    mb = synth.to_bf16_bits(m)
+    widened = (mb.astype(np.uint32) << 16).view(np.float32)
+    assert np.array_equal(oracle.frame_gradient(mb), oracle.frame_gradient(widened))
+
+
+# ------------------------------------------------------ cumulative variation (Eq. (11))
+
+def test_cumulative_variation_is_the_sum_of_l1_distances():
+    rng = np.random.default_rng(71)
+    n = 5003
+    cur = rng.standard_normal(n).astype(np.float32)
+    prevs = (cur[None, :] + rng.standard_normal((4, n)) * [[0.0], [0.1], [0.2], [0.4]]).astype(np.float32)
+    out = oracle.cumulative_variation(cur, prevs)
+    assert out.shape == (5,) and out[0] == 0.0            # a step compared with itself
+    for c in range(4):
+        ref = math.fsum(np.abs(cur.astype(np.float64) - prevs[c].astype(np.float64)))
+        assert abs(out[c] - ref) <= 1e-12 * max(ref, 1.0)
+        # and it is what the latent change of Eq. (5) reports for the same pair
+        assert out[c] == oracle.latent_delta(cur, prevs[c])[0]
+    assert abs(out[4] - math.fsum(out[:4])) <= 1e-12 * out[4]
+    assert out[1] < out[2] < out[3]
+    # integer grid: exact
+    ints = rng.integers(-50, 50, size=1000).astype(np.float32)
+    out = oracle.cumulative_variation(ints, np.stack([ints + 1, ints - 2]).astype(np.float32))
+    assert out.tolist() == [1000.0, 2000.0, 3000.0]
+
+
+# ------------------------------------------------------ threshold rules (Eq. (6), (8), (10))
+
+def test_threshold_rules_cover_each_case_and_each_boundary():
+    # Eq. (6): the lower threshold belongs to the middle case, the upper to the last
+    args = (0.1, 0.5, 8, 4, 2)
+    assert [oracle.cache_interval(d, *args) for d in (0.0, 0.0999, 0.1, 0.3, 0.4999, 0.5, 9.0)] == \
+        [8, 8, 4, 4, 4, 2, 2]
+    # Eq. (8) has the same shape
+    args = (1.0, 2.0, 8, 6, 4)
+    assert [oracle.activation_bits(d, *args) for d in (0.5, 1.0, 1.5, 2.0, 3.0)] == [8, 6, 6, 4, 4]
+    # Eq. (10): both thresholds belong to the middle case
+    args = (0.8, 0.95, 0.25)
+    assert [oracle.prune_probability(s, *args) for s in (0.5, 0.8, 0.9, 0.95, 0.951, 1.0)] == \
+        [0.0, 0.25, 0.25, 0.25, 1.0, 1.0]
+    # Eq. (5): per-step change times the gradient norm
+    assert oracle.divergence_score(12.0, 3, 0.5) == 2.0
+    assert oracle.divergence_score(12.0, 1, 2.0) == 24.0
