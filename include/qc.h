@@ -52,6 +52,8 @@ typedef enum { QC_OUT_F32 = 0, QC_OUT_BF16 = 1, QC_OUT_I32_ACC = 2 } qc_out;
 
 /* Largest reduction length: 127 * 127 * K must stay below 2^31. */
 #define QC_MAX_K 131072
+/* Most earlier tensors one qc_cumulative_variation call compares against. */
+#define QC_MAX_PREV 8
 
 const char *qc_status_string(qc_status status);
 /* Library ABI version (major * 1000 + minor). */
@@ -174,8 +176,7 @@ qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float 
 
 /* ---- cosine similarity of the features of consecutive layers -----------------------------
  * Section 3.3 SRAP, Eq. (9): S = <a, b> / (||a|| ||b||), the score the layer-pruning rule of
- * Eq. (10) thresholds.  (The cumulative variation of Eq. (11) is a sum of qc_latent_delta's
- * first output over the cached steps.)
+ * Eq. (10) thresholds.
  *   a, b       device, [n] of `dt` (float or bf16)
  *   out4       device, float [4]: { <a,b>, <a,a>, <b,b>, S };  S = 0 if either norm is 0
  *   workspace  device, >= qc_layer_similarity_workspace_bytes(n) bytes, 256-byte aligned,
@@ -184,6 +185,60 @@ qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float 
 size_t qc_layer_similarity_workspace_bytes(int64_t n);
 qc_status qc_layer_similarity(const void *a, const void *b, qc_dtype dt, int64_t n, float *out4,
                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- inter-frame gradient norm of a feature map -------------------------------------------
+ * Section 3.2 HLC, Eq. (5), second factor.  The paper names this factor without defining it;
+ * this library takes the forward difference along the frame axis and the Euclidean norm:
+ *   g[f, j] = m[f+1, j] - m[f, j]  (f < frames-1),   out2 = { sum g^2, sqrt(sum g^2) }.
+ *   m          device, [frames, inner] of `dt` (float or bf16), dense.  inner a multiple of 8
+ *              takes the vectorised path; any inner >= 1 is accepted.  frames = 1 gives zeros.
+ *   out2       device, float [2]
+ *   workspace  device, >= qc_frame_gradient_norm_workspace_bytes(frames, inner) bytes, 256-byte
+ *              aligned, contents irrelevant on entry
+ * Deterministic like qc_latent_delta.  Errors: INVALID_ARG, WORKSPACE, DEVICE. */
+size_t qc_frame_gradient_norm_workspace_bytes(int64_t frames, int64_t inner);
+qc_status qc_frame_gradient_norm(const void *m, qc_dtype dt, int64_t frames, int64_t inner,
+                                 float *out2, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/* ---- cumulative feature variation over the previous steps ---------------------------------
+ * Section 3.3 SRAP, Eq. (11): V = sum_i ||p_t - p_{t-i}||_1 over the kept earlier steps (the
+ * i = 0 term is zero and has no input here).  One pass reads `cur` once for all distances.
+ *   cur        device, float [n]
+ *   prevs      HOST array of `count` device pointers, each float [n]; read during the call
+ *              only.  1 <= count <= QC_MAX_PREV, else UNSUPPORTED
+ *   out        device, float [count + 1]: the L1 distance to each prevs[i], then V, their sum
+ *              in index order
+ *   workspace  device, >= qc_cumulative_variation_workspace_bytes(n, count) bytes, 256-byte
+ *              aligned, contents irrelevant on entry
+ * Deterministic like qc_latent_delta.  out[i] agrees with qc_latent_delta's first output for
+ * (cur, prevs[i]) to binary32 rounding; identical bits are not promised (the summation order
+ * differs).  Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, DEVICE. */
+size_t qc_cumulative_variation_workspace_bytes(int64_t n, int count);
+qc_status qc_cumulative_variation(const float *cur, const float *const *prevs, int count,
+                                  int64_t n, float *out, void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/* ---- decision rules (host, pure functions) ------------------------------------------------
+ * The scalar rules that turn the reductions above into the method's decisions.  All
+ * arguments and results are host values; nothing touches the GPU.  A NaN argument, or
+ * thresholds given in the wrong order (low > high), is an error: the integer rules then
+ * return -1, the floating-point rules NaN.
+ *
+ * qc_divergence_score   Section 3.2 HLC, Eq. (5): D = l1_change / k * grad_norm, with
+ *                       l1_change = qc_latent_delta's first output, k >= 1 the number of steps
+ *                       since the cached one, grad_norm = qc_frame_gradient_norm's second.
+ * qc_cache_interval     Eq. (6): tau_max if D < delta1, tau_mid if delta1 <= D < delta2,
+ *                       tau_min if D >= delta2.
+ * qc_activation_bits    Section 3.2 AIGQ (2), Eq. (8), the same three-way rule on the
+ *                       timestep's redundancy metric: bit_max below theta1, bit_mid from theta1
+ *                       up to theta2, bit_min from theta2 on.
+ * qc_prune_probability  Section 3.3 SRAP, Eq. (10): 1 if S > tau_high, 0 if S < tau_low,
+ *                       p_base on the closed interval between. */
+float qc_divergence_score(float l1_change, int k, float grad_norm);
+int qc_cache_interval(float D, float delta1, float delta2, int tau_max, int tau_mid, int tau_min);
+int qc_activation_bits(float D, float theta1, float theta2, int bit_max, int bit_mid, int bit_min);
+float qc_prune_probability(float S, float tau_low, float tau_high, float p_base);
 
 #ifdef __cplusplus
 }

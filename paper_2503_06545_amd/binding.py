@@ -25,6 +25,9 @@ EXPORTS = (
     "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_quant_act_bits",
     "qc_qlinear_quant_bits", "qc_qlinear_act_bits", "qc_layer_similarity_workspace_bytes",
     "qc_layer_similarity", "qc_debug_workspace_act", "qc_latent_delta",
+    "qc_frame_gradient_norm_workspace_bytes", "qc_frame_gradient_norm",
+    "qc_cumulative_variation_workspace_bytes", "qc_cumulative_variation",
+    "qc_divergence_score", "qc_cache_interval", "qc_activation_bits", "qc_prune_probability",
 )
 
 
@@ -82,6 +85,23 @@ def lib() -> ctypes.CDLL:
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+        f32 = ctypes.c_float
+        L.qc_frame_gradient_norm_workspace_bytes.restype = sz
+        L.qc_frame_gradient_norm_workspace_bytes.argtypes = [i64, i64]
+        L.qc_frame_gradient_norm.restype = i32
+        L.qc_frame_gradient_norm.argtypes = [vp, i32, i64, i64, vp, vp, sz, vp]
+        L.qc_cumulative_variation_workspace_bytes.restype = sz
+        L.qc_cumulative_variation_workspace_bytes.argtypes = [i64, i32]
+        L.qc_cumulative_variation.restype = i32
+        L.qc_cumulative_variation.argtypes = [vp, ctypes.POINTER(vp), i32, i64, vp, vp, sz, vp]
+        L.qc_divergence_score.restype = f32
+        L.qc_divergence_score.argtypes = [f32, i32, f32]
+        L.qc_cache_interval.restype = i32
+        L.qc_cache_interval.argtypes = [f32, f32, f32, i32, i32, i32]
+        L.qc_activation_bits.restype = i32
+        L.qc_activation_bits.argtypes = [f32, f32, f32, i32, i32, i32]
+        L.qc_prune_probability.restype = f32
+        L.qc_prune_probability.argtypes = [f32, f32, f32, f32]
         _lib = L
     return _lib
 
@@ -168,6 +188,44 @@ def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) ->
 
 
 # ---- tensor helpers: allocate outputs with torch, pass addresses and the current stream ----
+
+def qc_frame_gradient_norm_workspace_bytes(frames: int, inner: int) -> int:
+    return int(lib().qc_frame_gradient_norm_workspace_bytes(frames, inner))
+
+
+def qc_frame_gradient_norm(m, dt, frames, inner, out2, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_frame_gradient_norm(m, dt, frames, inner, out2, workspace,
+                                            workspace_bytes, stream))
+
+
+def qc_cumulative_variation_workspace_bytes(n: int, count: int) -> int:
+    return int(lib().qc_cumulative_variation_workspace_bytes(n, count))
+
+
+def qc_cumulative_variation(cur, prevs, count, n, out, workspace, workspace_bytes, stream=0) -> int:
+    """prevs: a sequence of `count` device addresses (or None for a null list)."""
+    arr = None
+    if prevs is not None:
+        arr = (ctypes.c_void_p * len(prevs))(*prevs)
+    return int(lib().qc_cumulative_variation(cur, arr, count, n, out, workspace, workspace_bytes,
+                                             stream))
+
+
+def qc_divergence_score(l1_change: float, k: int, grad_norm: float) -> float:
+    return float(lib().qc_divergence_score(l1_change, k, grad_norm))
+
+
+def qc_cache_interval(D, delta1, delta2, tau_max, tau_mid, tau_min) -> int:
+    return int(lib().qc_cache_interval(D, delta1, delta2, tau_max, tau_mid, tau_min))
+
+
+def qc_activation_bits(D, theta1, theta2, bit_max, bit_mid, bit_min) -> int:
+    return int(lib().qc_activation_bits(D, theta1, theta2, bit_max, bit_mid, bit_min))
+
+
+def qc_prune_probability(S, tau_low, tau_high, p_base) -> float:
+    return float(lib().qc_prune_probability(S, tau_low, tau_high, p_base))
+
 
 def _torch():
     import torch
@@ -304,3 +362,41 @@ def layer_similarity_t(a, b, workspace=None, out4=None):
                                workspace.data_ptr(), workspace.numel(), _stream()),
            "qc_layer_similarity")
     return out4
+
+
+def frame_gradient_norm_t(m, workspace=None, out2=None):
+    """m: [frames, ...] float32 or bfloat16, contiguous -> device float [2]."""
+    torch = _torch()
+    assert m.is_cuda and m.is_contiguous() and m.dim() >= 2
+    frames = m.shape[0]
+    inner = m.numel() // frames
+    if workspace is None:
+        workspace = torch.empty(qc_frame_gradient_norm_workspace_bytes(frames, inner),
+                                dtype=torch.uint8, device=m.device)
+    if out2 is None:
+        out2 = torch.empty(2, dtype=torch.float32, device=m.device)
+    _check(qc_frame_gradient_norm(m.data_ptr(), _xdt(m), frames, inner, out2.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), _stream()),
+           "qc_frame_gradient_norm")
+    return out2
+
+
+def cumulative_variation_t(cur, prevs, workspace=None, out=None):
+    """cur float32 [n], prevs a list of float32 tensors of the same size -> device float
+    [len(prevs) + 1]."""
+    torch = _torch()
+    assert cur.is_cuda and cur.is_contiguous() and cur.dtype == torch.float32
+    n = cur.numel()
+    for p in prevs:
+        assert p.is_cuda and p.is_contiguous() and p.dtype == torch.float32 and p.numel() == n
+    count = len(prevs)
+    if workspace is None:
+        workspace = torch.empty(max(qc_cumulative_variation_workspace_bytes(n, count), 256),
+                                dtype=torch.uint8, device=cur.device)
+    if out is None:
+        out = torch.empty(count + 1, dtype=torch.float32, device=cur.device)
+    _check(qc_cumulative_variation(cur.data_ptr(), [p.data_ptr() for p in prevs], count, n,
+                                   out.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                   _stream()),
+           "qc_cumulative_variation")
+    return out

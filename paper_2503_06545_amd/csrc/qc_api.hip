@@ -19,7 +19,44 @@ extern "C" const char *qc_status_string(qc_status status) {
     return "unknown qc_status";
 }
 
-extern "C" int qc_version(void) { return 1000; }
+extern "C" int qc_version(void) { return 1001; }
+
+// ---- decision rules: host arithmetic only ---------------------------------------------------
+
+namespace {
+// 0, 1, 2 for value < low, low <= value < high, value >= high; -1 for NaN or low > high
+int three_way(float value, float low, float high) {
+    if (value != value || low != low || high != high || low > high) return -1;
+    if (value < low) return 0;
+    return value < high ? 1 : 2;
+}
+}  // namespace
+
+extern "C" float qc_divergence_score(float l1_change, int k, float grad_norm) {
+    if (k < 1) return __builtin_nanf("");
+    return (float)((double)l1_change / (double)k * (double)grad_norm);
+}
+
+extern "C" int qc_cache_interval(float D, float delta1, float delta2, int tau_max, int tau_mid,
+                                 int tau_min) {
+    const int which = three_way(D, delta1, delta2);
+    return which < 0 ? -1 : which == 0 ? tau_max : which == 1 ? tau_mid : tau_min;
+}
+
+extern "C" int qc_activation_bits(float D, float theta1, float theta2, int bit_max, int bit_mid,
+                                  int bit_min) {
+    const int which = three_way(D, theta1, theta2);
+    return which < 0 ? -1 : which == 0 ? bit_max : which == 1 ? bit_mid : bit_min;
+}
+
+extern "C" float qc_prune_probability(float S, float tau_low, float tau_high, float p_base) {
+    if (S != S || tau_low != tau_low || tau_high != tau_high || p_base != p_base ||
+        tau_low > tau_high)
+        return __builtin_nanf("");
+    if (S > tau_high) return 1.0f;
+    if (S < tau_low) return 0.0f;
+    return p_base;
+}
 
 extern "C" size_t qc_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M < 1 || K < 1 || N < 1 || K > QC_MAX_K) return 0;

@@ -204,6 +204,149 @@ __global__ __launch_bounds__(kThreads) void similarity_final_kernel(
     }
 }
 
+// block-wide sum of one value; result valid in thread 0.  sh holds kThreads / 64 doubles.
+__device__ inline double block_sum1(double v, double *sh) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        v = sh[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) v += sh[w];
+    }
+    return v;
+}
+
+// ---- inter-frame gradient norm (Section 3.2 HLC, second factor of Eq. (5)) -----------------
+// The feature map is [frames, inner]; the gradient is the forward difference along the frame
+// axis and the norm is Euclidean.  As a reduction it is a pass over the pair (m, m + inner):
+// every element is read twice, the second time one frame (inner elements) later, which the
+// caches absorb for the frame sizes of a latent.
+
+__device__ inline float widen(float v) { return v; }
+__device__ inline float widen(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+
+// VEC: inner is a multiple of 8, so both streams can be read 8 elements at a time.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kThreads) void gradient_partial_kernel(
+    const T *__restrict__ m, int64_t inner, int64_t n, double *__restrict__ partials) {
+    __shared__ double sh[kThreads / 64];
+    const T *lo = m, *hi = m + inner;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t first = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    double ss = 0.0;
+    int64_t done = 0;
+    if constexpr (VEC) {
+        const int64_t n8 = n / 8;
+        for (int64_t i = first; i < n8; i += 2 * stride) {
+            Oct<T> x[2], y[2];
+            const bool second = i + stride < n8;
+            x[0].load(lo + 8 * i);
+            y[0].load(hi + 8 * i);
+            if (second) { x[1].load(lo + 8 * (i + stride)); y[1].load(hi + 8 * (i + stride)); }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (u == 1 && !second) break;
+                float p[2] = {0.f, 0.f};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {  // two 4-term binary32 sums
+                    const float d = y[u].get(e) - x[u].get(e);
+                    p[e >> 2] += d * d;
+                }
+                ss += (double)p[0] + (double)p[1];
+            }
+        }
+        done = n8 * 8;
+    }
+    for (int64_t j = done + first; j < n; j += stride) {
+        const float d = widen(hi[j]) - widen(lo[j]);
+        ss += (double)(d * d);
+    }
+    ss = block_sum1(ss, sh);
+    if (threadIdx.x == 0) partials[blockIdx.x] = ss;
+}
+
+__global__ __launch_bounds__(kThreads) void gradient_final_kernel(
+    const double *__restrict__ partials, int count, float *__restrict__ out2) {
+    __shared__ double sh[kThreads / 64];
+    double ss = 0.0;
+    for (int b = threadIdx.x; b < count; b += kThreads) ss += partials[b];
+    ss = block_sum1(ss, sh);
+    if (threadIdx.x == 0) {
+        out2[0] = (float)ss;
+        out2[1] = (float)sqrt(ss);
+    }
+}
+
+// ---- cumulative variation over the previous steps (Section 3.3 SRAP, Eq. (11)) --------------
+// L1 distance of the current tensor to each of COUNT earlier ones in one pass: the current
+// tensor is read once, not once per distance.
+
+struct PrevList { const float *p[QC_MAX_PREV]; };
+
+template <int COUNT>
+__global__ __launch_bounds__(kThreads) void variation_partial_kernel(
+    const float *__restrict__ cur, PrevList prevs, int64_t n, double *__restrict__ partials) {
+    __shared__ double sh[kThreads / 64];
+    const int64_t n4 = n / 4;
+    const float4 *c4 = reinterpret_cast<const float4 *>(cur);
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    double d[COUNT];
+#pragma unroll
+    for (int c = 0; c < COUNT; ++c) d[c] = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += 2 * stride) {
+        const bool second = i + stride < n4;
+        const int64_t i1 = second ? i + stride : i;  // a valid index either way
+        const float4 a0 = c4[i], a1 = c4[i1];
+        float4 b0[COUNT], b1[COUNT];
+#pragma unroll
+        for (int c = 0; c < COUNT; ++c) {
+            const float4 *p4 = reinterpret_cast<const float4 *>(prevs.p[c]);
+            b0[c] = p4[i];
+            b1[c] = p4[i1];
+        }
+#pragma unroll
+        for (int c = 0; c < COUNT; ++c) {
+            d[c] += (double)abs4(a0, b0[c]);
+            if (second) d[c] += (double)abs4(a1, b1[c]);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {  // up to 3 trailing elements
+        const int64_t j = n4 * 4 + threadIdx.x;
+#pragma unroll
+        for (int c = 0; c < COUNT; ++c) d[c] += (double)fabsf(cur[j] - prevs.p[c][j]);
+    }
+#pragma unroll
+    for (int c = 0; c < COUNT; ++c) {
+        const double t = block_sum1(d[c], sh);
+        if (threadIdx.x == 0) partials[(int64_t)blockIdx.x * QC_MAX_PREV + c] = t;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void variation_final_kernel(
+    const double *__restrict__ partials, int blocks, int count, float *__restrict__ out) {
+    __shared__ double sh[kThreads / 64];
+    double total = 0.0;
+    for (int c = 0; c < count; ++c) {
+        double v = 0.0;
+        for (int b = threadIdx.x; b < blocks; b += kThreads) v += partials[(int64_t)b * QC_MAX_PREV + c];
+        v = block_sum1(v, sh);
+        if (threadIdx.x == 0) {
+            out[c] = (float)v;
+            total += v;
+        }
+    }
+    if (threadIdx.x == 0) out[count] = (float)total;
+}
+
+template <int COUNT>
+void launch_variation(const float *cur, const PrevList &prevs, int64_t n, double *partials,
+                      unsigned blocks, hipStream_t stream) {
+    variation_partial_kernel<COUNT><<<dim3(blocks), dim3(kThreads), 0, stream>>>(cur, prevs, n, partials);
+}
+
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 }  // namespace
@@ -260,5 +403,77 @@ extern "C" qc_status qc_layer_similarity(const void *a, const void *b, qc_dtype 
             (const float *)a, (const float *)b, n, partials);
     if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
     similarity_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(partials, (int)blocks, out4);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" size_t qc_frame_gradient_norm_workspace_bytes(int64_t frames, int64_t inner) {
+    if (frames < 1 || inner < 1) return 0;
+    return (size_t)kMaxBlocks * sizeof(double);
+}
+
+extern "C" qc_status qc_frame_gradient_norm(const void *m, qc_dtype dt, int64_t frames,
+                                            int64_t inner, float *out2, void *workspace,
+                                            size_t workspace_bytes, void *stream) {
+    if (!m || !out2 || !workspace || frames < 1 || inner < 1) return QC_ERR_INVALID_ARG;
+    if (dt != QC_F32 && dt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(m, 16) || !aligned(out2, 4) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    if (frames > INT64_MAX / inner) return QC_ERR_INVALID_ARG;
+    if (workspace_bytes < qc_frame_gradient_norm_workspace_bytes(frames, inner)) return QC_ERR_WORKSPACE;
+    const int64_t n = (frames - 1) * inner;  // number of differences
+    const bool vec = inner % 8 == 0;
+    const int64_t per_block = (int64_t)kThreads * (vec ? 16 : 4);
+    int64_t blocks = (n + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;
+    if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+    double *partials = (double *)workspace;
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == QC_BF16) {
+        if (vec) gradient_partial_kernel<uint16_t, true><<<grid, block, 0, st>>>((const uint16_t *)m, inner, n, partials);
+        else gradient_partial_kernel<uint16_t, false><<<grid, block, 0, st>>>((const uint16_t *)m, inner, n, partials);
+    } else {
+        if (vec) gradient_partial_kernel<float, true><<<grid, block, 0, st>>>((const float *)m, inner, n, partials);
+        else gradient_partial_kernel<float, false><<<grid, block, 0, st>>>((const float *)m, inner, n, partials);
+    }
+    if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
+    gradient_final_kernel<<<dim3(1), block, 0, st>>>(partials, (int)blocks, out2);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" size_t qc_cumulative_variation_workspace_bytes(int64_t n, int count) {
+    if (n < 1 || count < 1 || count > QC_MAX_PREV) return 0;
+    return (size_t)kMaxBlocks * QC_MAX_PREV * sizeof(double);
+}
+
+extern "C" qc_status qc_cumulative_variation(const float *cur, const float *const *prevs, int count,
+                                             int64_t n, float *out, void *workspace,
+                                             size_t workspace_bytes, void *stream) {
+    if (!cur || !prevs || !out || !workspace || n < 1 || count < 1) return QC_ERR_INVALID_ARG;
+    if (count > QC_MAX_PREV) return QC_ERR_UNSUPPORTED;
+    if (!aligned(cur, 16) || !aligned(out, 4) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    PrevList list;
+    for (int c = 0; c < QC_MAX_PREV; ++c) {
+        list.p[c] = c < count ? prevs[c] : nullptr;
+        if (c < count && (!prevs[c] || !aligned(prevs[c], 16))) return QC_ERR_INVALID_ARG;
+    }
+    if (workspace_bytes < qc_cumulative_variation_workspace_bytes(n, count)) return QC_ERR_WORKSPACE;
+    int64_t blocks = (n / 4 + (int64_t)kThreads * 2 - 1) / ((int64_t)kThreads * 2);
+    if (blocks < 1) blocks = 1;
+    if (blocks > kMaxBlocks) blocks = kMaxBlocks;
+    double *partials = (double *)workspace;
+    hipStream_t st = (hipStream_t)stream;
+    const unsigned g = (unsigned)blocks;
+    switch (count) {
+        case 1: launch_variation<1>(cur, list, n, partials, g, st); break;
+        case 2: launch_variation<2>(cur, list, n, partials, g, st); break;
+        case 3: launch_variation<3>(cur, list, n, partials, g, st); break;
+        case 4: launch_variation<4>(cur, list, n, partials, g, st); break;
+        case 5: launch_variation<5>(cur, list, n, partials, g, st); break;
+        case 6: launch_variation<6>(cur, list, n, partials, g, st); break;
+        case 7: launch_variation<7>(cur, list, n, partials, g, st); break;
+        default: launch_variation<8>(cur, list, n, partials, g, st); break;
+    }
+    if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
+    variation_final_kernel<<<dim3(1), dim3(kThreads), 0, st>>>(partials, (int)blocks, count, out);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert qc.qc_version() == 1000
+    assert qc.qc_version() == 1001
     assert qc.status_string(0) == "QC_OK"
     for s in range(1, 5):
         assert qc.status_string(s).startswith("QC_ERR_")
@@ -85,6 +85,19 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_layer_similarity(A, A, 5, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_layer_similarity(A, A, qc.QC_BF16, 8, A, A, 8) == qc.QC_ERR_WORKSPACE
     assert qc.qc_layer_similarity_workspace_bytes(100) == 256 * 24
+    assert qc.qc_frame_gradient_norm(None, qc.QC_F32, 4, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_frame_gradient_norm(A, qc.QC_F32, 0, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_frame_gradient_norm(A, 5, 4, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_frame_gradient_norm(A, qc.QC_F32, 4, 16, A, A, 8) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_cumulative_variation(A, [A], 1, 0, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_cumulative_variation(A, None, 1, 64, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_cumulative_variation(A, [A, None], 2, 64, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_cumulative_variation(A, [A, A + 4], 2, 64, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_cumulative_variation(A, [A] * 9, 9, 64, A, A, 1 << 20) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_cumulative_variation(A, [A] * 8, 8, 64, A, A, 64) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_frame_gradient_norm_workspace_bytes(16, 1152) == 256 * 8
+    assert qc.qc_cumulative_variation_workspace_bytes(1 << 20, 3) == 256 * 8 * 8
+    assert qc.qc_cumulative_variation_workspace_bytes(1 << 20, 9) == 0
 
 
 def test_missing_library_is_a_loud_error(monkeypatch):
@@ -92,3 +105,35 @@ def test_missing_library_is_a_loud_error(monkeypatch):
     monkeypatch.setattr(qc, "LIB_PATH", "/nonexistent/libqc.so")
     with pytest.raises(ImportError):
         qc.lib()
+
+
+def test_decision_rules_match_the_oracle_on_every_case_and_boundary():
+    """Eq. (5), (6), (8), (10): host arithmetic, checked against the oracle's plain definitions."""
+    import math
+
+    import numpy as np
+
+    import oracle
+    f = lambda v: float(np.float32(v))
+    grid = [f(v) for v in (-1.0, 0.0, 0.0999, 0.1, 0.3, 0.4999, 0.5, 0.8, 0.95, 0.951, 1.0, 9.0)]
+    for d in grid:
+        a = (f(0.1), f(0.5), 8, 4, 2)
+        assert qc.qc_cache_interval(d, *a) == oracle.cache_interval(d, *a)
+        b = (f(0.3), f(0.95), 8, 6, 4)
+        assert qc.qc_activation_bits(d, *b) == oracle.activation_bits(d, *b)
+        c = (f(0.8), f(0.95), f(0.25))
+        assert qc.qc_prune_probability(d, *c) == oracle.prune_probability(d, *c)
+    # equal thresholds: the middle case is empty for Eq. (6) and (8), a point for Eq. (10)
+    assert qc.qc_cache_interval(0.5, 0.5, 0.5, 8, 4, 2) == oracle.cache_interval(0.5, 0.5, 0.5, 8, 4, 2) == 2
+    assert qc.qc_prune_probability(0.5, 0.5, 0.5, 0.25) == oracle.prune_probability(0.5, 0.5, 0.5, 0.25) == 0.25
+    for l1, k, g in [(12.0, 3, 0.5), (1e6, 7, 3.25), (0.0, 1, 5.0)]:
+        want = np.float32(oracle.divergence_score(l1, k, g))
+        assert np.float32(qc.qc_divergence_score(l1, k, g)) == want
+    # error behaviour: NaN or thresholds in the wrong order
+    nan = float("nan")
+    assert qc.qc_cache_interval(nan, 0.1, 0.5, 8, 4, 2) == -1
+    assert qc.qc_cache_interval(0.2, 0.5, 0.1, 8, 4, 2) == -1
+    assert qc.qc_activation_bits(0.2, nan, 0.5, 8, 6, 4) == -1
+    assert math.isnan(qc.qc_prune_probability(nan, 0.8, 0.95, 0.25))
+    assert math.isnan(qc.qc_prune_probability(0.9, 0.95, 0.8, 0.25))
+    assert math.isnan(qc.qc_divergence_score(1.0, 0, 1.0))

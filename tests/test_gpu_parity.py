@@ -348,3 +348,62 @@ def test_layer_similarity_closed_forms():
     assert abs(qc.layer_similarity_t(a, a).cpu().tolist()[3] - 1.0) < 1e-6
     assert abs(qc.layer_similarity_t(a, -a).cpu().tolist()[3] + 1.0) < 1e-6
     assert qc.layer_similarity_t(a, torch.zeros_like(a)).cpu().tolist()[3] == 0.0
+
+
+# ------------------------------------------------------------------ qc_frame_gradient_norm
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("frames,inner", [(1, 64), (2, 1), (2, 8), (3, 7), (5, 1000), (16, 1152),
+                                          (16, 9 * 1152 + 4), (16, 256 * 1152), (51, 32 * 32 * 4)])
+def test_frame_gradient_norm_matches_oracle(dtype, frames, inner):
+    m, _ = synth.latent_pair(seed=(frames * 131 + inner) % 83, n=frames * inner)
+    m = m.reshape(frames, inner)
+    if dtype == "bf16":
+        m = synth.to_bf16_bits(m)
+    ref = oracle.frame_gradient(m)
+    got = qc.frame_gradient_norm_t(dev(m)).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 2e-6 * np.abs(ref)), (got, ref)
+    again = qc.frame_gradient_norm_t(dev(m)).cpu().numpy()
+    assert bits_equal(again, got.astype(np.float32))
+
+
+def test_frame_gradient_norm_closed_forms():
+    F, inner = 12, 4096 + 8
+    v = torch.randint(-8, 9, (inner,), device="cuda", dtype=torch.float32)
+    ramp = torch.arange(F, device="cuda", dtype=torch.float32)[:, None] * v[None, :] + 3.0
+    ss, norm = qc.frame_gradient_norm_t(ramp.contiguous()).cpu().tolist()
+    want = (F - 1) * float((v.double() ** 2).sum())
+    assert ss == np.float32(want) and abs(norm - math.sqrt(want)) <= 1e-6 * norm
+    still = torch.randn(inner, device="cuda").expand(F, inner).contiguous()
+    assert qc.frame_gradient_norm_t(still).cpu().tolist() == [0.0, 0.0]
+    # the same numbers as one tensor [F, inner] or as a bf16 copy of an integer ramp
+    assert qc.frame_gradient_norm_t(ramp.to(torch.bfloat16).contiguous()).cpu().tolist()[0] == \
+        oracle.frame_gradient(synth.to_bf16_bits(ramp.cpu().numpy()))[0].astype(np.float32)
+
+
+# ------------------------------------------------------------------ qc_cumulative_variation
+
+@pytest.mark.parametrize("count", [1, 2, 3, 5, 8])
+@pytest.mark.parametrize("n", [1, 3, 4, 6, 2049, 100003, 16 * 4 * 16 * 64 * 64])
+def test_cumulative_variation_matches_oracle(count, n):
+    cur, _ = synth.latent_pair(seed=n % 79, n=n)
+    prevs = np.stack([synth.latent_pair(seed=n % 79, n=n, delta=0.01 * (c + 1))[0]
+                      for c in range(count)])
+    ref = oracle.cumulative_variation(cur, prevs)
+    dp = [dev(prevs[c]) for c in range(count)]
+    got = qc.cumulative_variation_t(dev(cur), dp).cpu().numpy().astype(np.float64)
+    assert got.shape == (count + 1,)
+    assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-30), (got, ref)
+    again = qc.cumulative_variation_t(dev(cur), dp).cpu().numpy()
+    assert bits_equal(again, got.astype(np.float32))
+
+
+def test_cumulative_variation_agrees_with_latent_delta_and_closed_forms():
+    n = 1 << 20
+    cur = torch.randint(-50, 50, (n,), device="cuda", dtype=torch.float32)
+    out = qc.cumulative_variation_t(cur, [cur + 1, cur - 2, cur.clone()]).cpu().tolist()
+    assert out == [float(n), 2.0 * n, 0.0, 3.0 * n]
+    a, b = torch.randn(n, device="cuda"), torch.randn(n, device="cuda")
+    one = qc.cumulative_variation_t(a, [b]).cpu().numpy()
+    pair = qc.latent_delta_t(a, b).cpu().numpy()
+    assert abs(one[0] - pair[0]) <= 1e-6 * pair[0] and one[1] == one[0]
