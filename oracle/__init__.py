@@ -15,6 +15,9 @@ Paper passages each function follows (arxiv 2503.06545):
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
   layer_similarity          Section 3.3 SRAP, Eq. (9)
+  rotate_rows, quant_act_   Section 3.2 AIGQ (1) (rotation against outlier channels) and
+  rot, quant_weight_rot,    Section 4.1 "Hardware Implementation" (rotation fused with the
+  qlinear_rot               quantization), as a block Walsh-Hadamard transform over K
   frame_gradient,           Section 3.2 HLC, Eq. (5): the inter-frame gradient factor and the
   divergence_score          score built from it and latent_delta's first sum
   cumulative_variation      Section 3.3 SRAP, Eq. (11)
@@ -69,6 +72,8 @@ def _L():
         lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
         lib.orc_layer_similarity.argtypes = [vp, vp, i32, i64, vp]
         lib.orc_layer_similarity.restype = None
+        lib.orc_rotate_rows_f32.argtypes = [vp, i64, i64, i32, ctypes.c_float, vp]
+        lib.orc_rotate_rows_f32.restype = None
         lib.orc_frame_gradient.argtypes = [vp, i32, i64, i64, vp]
         lib.orc_frame_gradient.restype = None
         lib.orc_cumulative_variation.argtypes = [vp, vp, i32, i64, vp]
@@ -293,3 +298,41 @@ def prune_probability(S, tau_low, tau_high, p_base):
     if S < tau_low:
         return 0.0
     return float(p_base)
+
+
+# ---- rotation before quantization ------------------------------------------------------------
+
+def widen_f32(X):
+    """float32 view of the input values: bf16 bit patterns widened exactly, float32 as is."""
+    if X.dtype == np.uint16:
+        return (np.ascontiguousarray(X).astype(np.uint32) << 16).view(np.float32)
+    return _c(X, np.float32)
+
+
+def rotate_rows(X, block: int, post_scale: float = 1.0):
+    """Block Walsh-Hadamard transform of each row of X [R, K] (float32) over blocks of `block`
+    consecutive columns, binary32 butterflies in ascending stride, then * post_scale."""
+    X = _c(X, np.float32)
+    R, K = X.shape
+    if block < 2 or block & (block - 1) or K % block:
+        raise ValueError("block must be a power of two that divides K")
+    out = np.empty((R, K), np.float32)
+    _L().orc_rotate_rows_f32(_p(X), R, K, int(block), float(post_scale), _p(out))
+    return out
+
+
+def quant_act_rot(X, block: int, act_bits: int = 8):
+    """Per-token quantization of the rotated activations X H."""
+    return _quant_rows(rotate_rows(widen_f32(X), block), qmax(act_bits))
+
+
+def quant_weight_rot(W, bits: int, block: int):
+    """Per-channel quantization of the counter-rotated weights W H / block."""
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
+    return _quant_rows(rotate_rows(np.asarray(W, np.float32), block, 1.0 / block), qmax(bits))
+
+
+def qlinear_rot(X, qw, sw, block: int, bias=None, epi=EPI_NONE, act_bits: int = 8):
+    """The quantized linear on rotated activations; qw / sw come from quant_weight_rot."""
+    return qlinear(rotate_rows(widen_f32(X), block), qw, sw, bias, epi, act_bits)

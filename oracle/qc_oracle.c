@@ -25,7 +25,13 @@
  *     the tests; that it is the authors' definition cannot be checked from the
  *     paper: parity unpinned for this function in that sense;
  *   - Section 3.3 SRAP, Eq. (9) (cosine similarity of consecutive layers) and
- *     Eq. (11) (cumulative L1 variation over the previous steps).
+ *     Eq. (11) (cumulative L1 variation over the previous steps);
+ *   - Section 3.2 AIGQ (1) and Section 4.1 "Hardware Implementation": a rotation
+ *     applied together with the quantization.  The matrix is not given; the
+ *     reading here is a block Walsh-Hadamard transform (orc_rotate_rows_f32).
+ *     Its arithmetic is pinned (the explicit matrix, H H^T = block * I, the
+ *     unchanged product X W^T); which rotation the authors use is not:
+ *     parity unpinned in that sense.
  *
  * Arithmetic contract.  The steps marked [bit] are single IEEE-754 binary32
  * operations, round to nearest even, written one per statement so that no
@@ -313,4 +319,44 @@ void orc_cumulative_variation(const float *cur, const float *prevs, int count, i
         total += d;
     }
     out[count] = total;
+}
+
+/*
+ * Rotation before quantization (Section 3.2 AIGQ (1): a lightweight rotation evens out the
+ * channels; Section 4.1 "Hardware Implementation": it is fused with the quantization).  The
+ * paper does not give the matrix.  Reading taken here: a block-diagonal Walsh-Hadamard
+ * matrix over the reduction axis, blocks of `block` consecutive columns (a power of two that
+ * divides K), Sylvester (natural) order, entries +1 / -1.  Since H H^T = block * I, rotating
+ * the activations by H and the weights by H / block leaves X W^T unchanged.
+ *
+ * Arithmetic [bit]: the transform is evaluated as the fast butterfly network in binary32,
+ * stages in ascending stride h = 1, 2, 4, ..., block / 2; a stage replaces every pair
+ * (x[j], x[j + h]) with bit h of j clear by (x[j] + x[j + h], x[j] - x[j + h]), one rounding
+ * each.  The result is multiplied by post_scale (1, or the exact power of two 1 / block).
+ * The quantizer then decides codes on these binary32 values, so this order is part of the
+ * bit-exact contract with the GPU path.
+ */
+void orc_rotate_rows_f32(const float *X, int64_t R, int64_t K, int block, float post_scale,
+                         float *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r) {
+        const float *x = X + r * K;
+        float *y = out + r * K;
+        for (int64_t k = 0; k < K; ++k) y[k] = x[k];
+        for (int64_t b0 = 0; b0 + block <= K; b0 += block) {
+            float *v = y + b0;
+            for (int h = 1; h < block; h <<= 1)
+                for (int j = 0; j < block; ++j)
+                    if ((j & h) == 0) {
+                        volatile float sum = v[j] + v[j + h];
+                        volatile float dif = v[j] - v[j + h];
+                        v[j] = sum;
+                        v[j + h] = dif;
+                    }
+            for (int j = 0; j < block; ++j) {
+                volatile float scaled = v[j] * post_scale;
+                v[j] = scaled;
+            }
+        }
+    }
 }

@@ -484,3 +484,81 @@ def test_threshold_rules_cover_each_case_and_each_boundary():
     # Eq. (5): per-step change times the gradient norm
     assert oracle.divergence_score(12.0, 3, 0.5) == 2.0
     assert oracle.divergence_score(12.0, 1, 2.0) == 24.0
+
+
+# ------------------------------------------------------ rotation before quantization
+
+def sylvester(block: int) -> np.ndarray:
+    """The +1/-1 Walsh-Hadamard matrix in natural order, built by doubling."""
+    H = np.ones((1, 1))
+    while H.shape[0] < block:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+@pytest.mark.parametrize("block", [2, 16, 32, 64, 128])
+def test_rotation_is_the_block_hadamard_matrix(block):
+    import scipy.linalg
+    H = sylvester(block)
+    assert np.array_equal(H, scipy.linalg.hadamard(block))
+    assert np.array_equal(H @ H.T, block * np.eye(block)) and np.array_equal(H, H.T)
+    rng = np.random.default_rng(73 + block)
+    K = 3 * block
+    # small integers: every butterfly is exact, so the result is the matrix product exactly
+    xi = rng.integers(-9, 10, size=(5, K)).astype(np.float32)
+    want = np.concatenate([xi[:, b:b + block].astype(np.float64) @ H for b in range(0, K, block)], axis=1)
+    assert np.array_equal(oracle.rotate_rows(xi, block), want)
+    # a unit vector picks one row of H, sign pattern and order included
+    for j in (0, 1, block // 2, block - 1):
+        e = np.zeros((1, K), np.float32)
+        e[0, block + j] = 1.0
+        got = oracle.rotate_rows(e, block)
+        assert np.array_equal(got[0, block:2 * block], H[j]) and not got[0, :block].any()
+    # twice is block * identity; with post_scale 1/block it is the inverse
+    assert np.array_equal(oracle.rotate_rows(oracle.rotate_rows(xi, block), block, 1.0 / block), xi)
+    # real inputs: binary32 butterflies against the binary64 matrix product
+    xr = rng.standard_normal((7, K)).astype(np.float32)
+    want = np.concatenate([xr[:, b:b + block].astype(np.float64) @ H for b in range(0, K, block)], axis=1)
+    got = oracle.rotate_rows(xr, block)
+    assert np.max(np.abs(got - want)) <= 4e-7 * math.log2(block) * np.max(np.abs(want))
+    # energy: |x H|^2 = block |x|^2
+    assert abs((got.astype(np.float64) ** 2).sum() / (xr.astype(np.float64) ** 2).sum() - block) < 1e-5 * block
+
+
+def test_rotation_leaves_the_linear_unchanged_and_spreads_outliers():
+    rng = np.random.default_rng(79)
+    M, K, N, block = 24, 512, 40, 128
+    # integers: (X H)(W H / block)^T = X W^T exactly
+    xi = rng.integers(-6, 7, size=(M, K)).astype(np.float32)
+    wi = (rng.integers(-6, 7, size=(N, K)) * block).astype(np.float32)
+    xr = oracle.rotate_rows(xi, block)
+    wr = oracle.rotate_rows(wi, block, 1.0 / block)
+    assert np.array_equal(xr.astype(np.float64) @ wr.astype(np.float64).T,
+                          xi.astype(np.float64) @ wi.astype(np.float64).T)
+    # activations with a few outlier channels (20x), the case the rotation is for: the
+    # quantized linear is closer to the exact product with the rotation than without it
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X[:, rng.choice(K, 6, replace=False)] *= 20.0
+    W = (0.02 * rng.standard_normal((N, K))).astype(np.float32)
+    exact = X.astype(np.float64) @ W.astype(np.float64).T
+    for bits in (8, 4):
+        qw, sw = oracle.quant_weight(W, bits)
+        plain = oracle.qlinear(X, qw, sw)["y"]
+        qwr, swr = oracle.quant_weight_rot(W, bits, block)
+        rot = oracle.qlinear_rot(X, qwr, swr, block)["y"]
+        err = lambda y: np.sqrt(np.mean((y - exact) ** 2)) / np.sqrt(np.mean(exact ** 2))
+        assert err(rot) < err(plain) and err(rot) < (0.02 if bits == 8 else 0.2)
+    # 4-bit activations gain the most
+    qw, sw = oracle.quant_weight(W, 8)
+    qwr, swr = oracle.quant_weight_rot(W, 8, block)
+    e_plain = np.abs(oracle.qlinear(X, qw, sw, act_bits=4)["y"] - exact).mean()
+    e_rot = np.abs(oracle.qlinear_rot(X, qwr, swr, block, act_bits=4)["y"] - exact).mean()
+    assert e_rot < 0.5 * e_plain
+    # the rotated activation codes are the quantizer applied to the rotated rows, bf16 input
+    # widened exactly first
+    from paper_2503_06545_amd import synth
+    Xb = synth.to_bf16_bits(X)
+    q1, s1 = oracle.quant_act_rot(Xb, block, 6)
+    q2, s2 = oracle.quant_act(oracle.rotate_rows(oracle.widen_f32(Xb), block), 6)
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    assert np.array_equal(oracle.widen_f32(Xb).astype(np.float64), oracle.bf16_bits_to_f64(Xb))
