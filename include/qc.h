@@ -154,6 +154,36 @@ qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                               const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- rotation fused into the quantization ------------------------------------------------
+ * Section 3.2 AIGQ (1): a lightweight rotation evens out the channels before quantization;
+ * Section 4.1 "Hardware Implementation": the rotation is fused with the quantization kernel.
+ * The paper does not give the matrix.  Here it is block diagonal over the reduction axis:
+ * every run of `rot_block` consecutive columns (16, 32, 64 or 128; K a multiple of it) is
+ * multiplied by the Walsh-Hadamard matrix H of that size (entries +1/-1, natural order).
+ * Activations become X H before their absmax and cast, inside the quantization kernel;
+ * qc_pack_weight_rot stores the codes of W H / rot_block, so that the product is unchanged:
+ * (X H)(W H / rot_block)^T = X W^T.  H is applied as a butterfly network in binary32 with
+ * strides 1, 2, 4, .. in ascending order (one rounding per output per stage); that order is
+ * part of the bit-exact contract.
+ *   qc_pack_weight_rot    qc_pack_weight on the counter-rotated weights
+ *   qc_quant_act_rot      qc_quant_act_bits on the rotated activations
+ *   qc_qlinear_quant_rot  qc_qlinear_quant_bits on the rotated activations
+ *   qc_qlinear_rot        qc_qlinear_quant_rot then qc_qlinear_gemm; `packed` / `w_scale` must
+ *                         come from qc_pack_weight_rot with the same rot_block (not checked)
+ * Other arguments and errors as for the calls they extend.  UNSUPPORTED: rot_block not one of
+ * 16/32/64/128, K not a multiple of it, or K > 9216. */
+qc_status qc_pack_weight_rot(const float *W, int64_t N, int64_t K, int bits, int rot_block,
+                             void *packed, float *w_scale, void *stream);
+qc_status qc_quant_act_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                           int rot_block, int8_t *qx, float *x_scale, void *stream);
+qc_status qc_qlinear_quant_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                               int rot_block, void *workspace, size_t workspace_bytes,
+                               void *stream);
+qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                         int rot_block, const void *packed, const float *w_scale, int bits,
+                         int64_t N, const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
  * activation codes and scales it used out of the workspace in canonical order:
  * qx int8 [M, K] row major, x_scale float [M]. */

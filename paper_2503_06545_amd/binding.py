@@ -28,6 +28,7 @@ EXPORTS = (
     "qc_frame_gradient_norm_workspace_bytes", "qc_frame_gradient_norm",
     "qc_cumulative_variation_workspace_bytes", "qc_cumulative_variation",
     "qc_divergence_score", "qc_cache_interval", "qc_activation_bits", "qc_prune_probability",
+    "qc_pack_weight_rot", "qc_quant_act_rot", "qc_qlinear_quant_rot", "qc_qlinear_rot",
 )
 
 
@@ -86,6 +87,15 @@ def lib() -> ctypes.CDLL:
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
         f32 = ctypes.c_float
+        L.qc_pack_weight_rot.restype = i32
+        L.qc_pack_weight_rot.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
+        L.qc_quant_act_rot.restype = i32
+        L.qc_quant_act_rot.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, vp]
+        L.qc_qlinear_quant_rot.restype = i32
+        L.qc_qlinear_quant_rot.argtypes = [vp, i32, i64, i64, i32, i32, vp, sz, vp]
+        L.qc_qlinear_rot.restype = i32
+        L.qc_qlinear_rot.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, i32, i64, vp, i32, vp, i32,
+                                     vp, sz, vp]
         L.qc_frame_gradient_norm_workspace_bytes.restype = sz
         L.qc_frame_gradient_norm_workspace_bytes.argtypes = [i64, i64]
         L.qc_frame_gradient_norm.restype = i32
@@ -189,6 +199,26 @@ def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) ->
 
 # ---- tensor helpers: allocate outputs with torch, pass addresses and the current stream ----
 
+def qc_pack_weight_rot(W, N, K, bits, rot_block, packed, w_scale, stream=0) -> int:
+    return int(lib().qc_pack_weight_rot(W, N, K, bits, rot_block, packed, w_scale, stream))
+
+
+def qc_quant_act_rot(X, xdt, M, K, act_bits, rot_block, qx, x_scale, stream=0) -> int:
+    return int(lib().qc_quant_act_rot(X, xdt, M, K, act_bits, rot_block, qx, x_scale, stream))
+
+
+def qc_qlinear_quant_rot(X, xdt, M, K, act_bits, rot_block, workspace, workspace_bytes,
+                         stream=0) -> int:
+    return int(lib().qc_qlinear_quant_rot(X, xdt, M, K, act_bits, rot_block, workspace,
+                                          workspace_bytes, stream))
+
+
+def qc_qlinear_rot(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                   workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_rot(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N,
+                                    bias, epi, Y, ydt, workspace, workspace_bytes, stream))
+
+
 def qc_frame_gradient_norm_workspace_bytes(frames: int, inner: int) -> int:
     return int(lib().qc_frame_gradient_norm_workspace_bytes(frames, inner))
 
@@ -261,7 +291,7 @@ class PackedWeight:
         self.blob, self.scale, self.N, self.K, self.bits = blob, scale, N, K, bits
 
 
-def pack_weight_t(W, bits: int) -> PackedWeight:
+def pack_weight_t(W, bits: int, rot_block: int = 0) -> PackedWeight:
     torch = _torch()
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.dim() == 2
     N, K = W.shape
@@ -270,8 +300,12 @@ def pack_weight_t(W, bits: int) -> PackedWeight:
         raise QcError(QC_ERR_UNSUPPORTED, "qc_packed_weight_bytes")
     blob = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
     scale = torch.empty(N, dtype=torch.float32, device=W.device)
-    _check(qc_pack_weight(W.data_ptr(), N, K, bits, blob.data_ptr(), scale.data_ptr(), _stream()),
-           "qc_pack_weight")
+    if rot_block:
+        _check(qc_pack_weight_rot(W.data_ptr(), N, K, bits, rot_block, blob.data_ptr(),
+                                  scale.data_ptr(), _stream()), "qc_pack_weight_rot")
+    else:
+        _check(qc_pack_weight(W.data_ptr(), N, K, bits, blob.data_ptr(), scale.data_ptr(),
+                              _stream()), "qc_pack_weight")
     return PackedWeight(blob, scale, N, K, bits)
 
 
@@ -283,14 +317,18 @@ def unpack_weight_codes_t(pw: PackedWeight):
     return codes
 
 
-def quant_act_t(X, act_bits: int = 8):
+def quant_act_t(X, act_bits: int = 8, rot_block: int = 0):
     torch = _torch()
     assert X.is_cuda and X.is_contiguous() and X.dim() == 2
     M, K = X.shape
     qx = torch.empty((M, K), dtype=torch.int8, device=X.device)
     sx = torch.empty(M, dtype=torch.float32, device=X.device)
-    _check(qc_quant_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, qx.data_ptr(), sx.data_ptr(),
-                             _stream()), "qc_quant_act_bits")
+    if rot_block:
+        _check(qc_quant_act_rot(X.data_ptr(), _xdt(X), M, K, act_bits, rot_block, qx.data_ptr(),
+                                sx.data_ptr(), _stream()), "qc_quant_act_rot")
+    else:
+        _check(qc_quant_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, qx.data_ptr(),
+                                 sx.data_ptr(), _stream()), "qc_quant_act_bits")
     return qx, sx
 
 
@@ -303,7 +341,7 @@ def qlinear_workspace_t(M: int, K: int, N: int, device="cuda"):
 
 
 def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=None, Y=None,
-              act_bits: int = 8):
+              act_bits: int = 8, rot_block: int = 0):
     torch = _torch()
     assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == pw.K
     M, K = X.shape
@@ -312,11 +350,17 @@ def qlinear_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=
     if Y is None:
         ydtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[out]
         Y = torch.empty((M, pw.N), dtype=ydtype, device=X.device)
-    _check(qc_qlinear_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, pw.blob.data_ptr(),
-                               pw.scale.data_ptr(), pw.bits, pw.N,
-                               None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
-                               OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
-           "qc_qlinear_act_bits")
+    b = None if bias is None else bias.data_ptr()
+    if rot_block:
+        _check(qc_qlinear_rot(X.data_ptr(), _xdt(X), M, K, act_bits, rot_block, pw.blob.data_ptr(),
+                              pw.scale.data_ptr(), pw.bits, pw.N, b, EPI[epi], Y.data_ptr(),
+                              OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
+               "qc_qlinear_rot")
+    else:
+        _check(qc_qlinear_act_bits(X.data_ptr(), _xdt(X), M, K, act_bits, pw.blob.data_ptr(),
+                                   pw.scale.data_ptr(), pw.bits, pw.N, b, EPI[epi], Y.data_ptr(),
+                                   OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
+               "qc_qlinear_act_bits")
     return Y
 
 

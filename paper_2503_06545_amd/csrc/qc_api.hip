@@ -67,16 +67,92 @@ namespace {
 bool act_bits_ok(int b) { return b == 8 || b == 6 || b == 4; }
 }  // namespace
 
-extern "C" qc_status qc_quant_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                       int act_bits, int8_t *qx, float *x_scale, void *stream) {
+namespace {
+// rot_block 0 = no rotation
+qc_status quant_act_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                        int rot_block, int8_t *qx, float *x_scale, void *stream) {
     if (!X || !qx || !x_scale || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
     if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
     if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
     if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
     if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, act_bits,
+    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
+    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, act_bits, rot_block,
                                     (hipStream_t)stream);
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+qc_status qlinear_quant_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                            int rot_block, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    uint8_t *base = (uint8_t *)workspace;
+    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
+                                    (float *)base, act_bits, rot_block, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+qc_status qlinear_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                      int rot_block, const void *packed, const float *w_scale, int bits, int64_t N,
+                      const float *bias, qc_epilogue epi, void *Y, qc_out ydt, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+    // every argument is checked before the first launch, so a failed call has no side effect
+    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
+        return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
+        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
+    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    qc_status st = qlinear_quant_any(X, xdt, M, K, act_bits, rot_block, workspace, workspace_bytes,
+                                     stream);
+    if (st != QC_OK) return st;
+    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
+                           ydt, stream);
+}
+}  // namespace
+
+extern "C" qc_status qc_quant_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                       int act_bits, int8_t *qx, float *x_scale, void *stream) {
+    return quant_act_any(X, xdt, M, K, act_bits, 0, qx, x_scale, stream);
+}
+
+extern "C" qc_status qc_quant_act_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                      int act_bits, int rot_block, int8_t *qx, float *x_scale,
+                                      void *stream) {
+    if (rot_block == 0) return QC_ERR_UNSUPPORTED;
+    return quant_act_any(X, xdt, M, K, act_bits, rot_block, qx, x_scale, stream);
+}
+
+extern "C" qc_status qc_qlinear_quant_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                          int act_bits, int rot_block, void *workspace,
+                                          size_t workspace_bytes, void *stream) {
+    if (rot_block == 0) return QC_ERR_UNSUPPORTED;
+    return qlinear_quant_any(X, xdt, M, K, act_bits, rot_block, workspace, workspace_bytes, stream);
+}
+
+extern "C" qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                                    int rot_block, const void *packed, const float *w_scale,
+                                    int bits, int64_t N, const float *bias, qc_epilogue epi, void *Y,
+                                    qc_out ydt, void *workspace, size_t workspace_bytes,
+                                    void *stream) {
+    if (rot_block == 0) return QC_ERR_UNSUPPORTED;
+    return qlinear_any(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N, bias, epi, Y,
+                       ydt, workspace, workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
@@ -87,17 +163,7 @@ extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_
 extern "C" qc_status qc_qlinear_quant_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                            int act_bits, void *workspace, size_t workspace_bytes,
                                            void *stream) {
-    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    const ActWorkspace ws = act_workspace(M, K);
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    uint8_t *base = (uint8_t *)workspace;
-    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
-                                    (float *)base, act_bits, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    return qlinear_quant_any(X, xdt, M, K, act_bits, 0, workspace, workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
@@ -132,25 +198,8 @@ extern "C" qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M,
                                          int bits, int64_t N, const float *bias, qc_epilogue epi,
                                          void *Y, qc_out ydt, void *workspace,
                                          size_t workspace_bytes, void *stream) {
-    // every argument is checked before the first launch, so a failed call has no side effect
-    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
-        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
-    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    const ActWorkspace ws = act_workspace(M, K);
-    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    qc_status st = qc_qlinear_quant_bits(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream);
-    if (st != QC_OK) return st;
-    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
-                           ydt, stream);
+    return qlinear_any(X, xdt, M, K, act_bits, 0, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                       workspace, workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,

@@ -67,9 +67,11 @@ __host__ inline ActWorkspace act_workspace(int64_t M, int64_t K) {
 
 // ---- launchers (each returns hipGetLastError() of its launch) --------------------------
 
+// rot_block: 0 for no rotation, else the Walsh-Hadamard block size (quant_rotation_supported)
 hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx_rowmajor,
                             uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
-                            hipStream_t stream);
+                            int rot_block, hipStream_t stream);
+bool quant_rotation_supported(int64_t K, int rot_block);
 
 hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8_t *w_packed,
                        const float *w_scale, const float *bias, void *Y, int64_t M, int64_t N,

@@ -24,9 +24,41 @@ __device__ __host__ inline int64_t w4_dword_offset(int64_t p, int64_t k8, int64_
 
 __device__ __host__ inline int w4_nibble_of(int e) { return e < 4 ? 2 * e : 2 * (e - 4) + 1; }
 
+// Eight consecutive weights of a row, k = k8 .. k8 + 7 (zeros past K or for a padding row),
+// after the counter-rotation that matches rotated activations (Section 3.2 AIGQ (1), Section
+// 4.1): each block of `rot` columns times the Walsh-Hadamard matrix, then times 1 / rot.  Same
+// butterfly network as the activation side, binary32, strides ascending: 1, 2, 4 inside the
+// lane's eight values, 8 .. rot / 2 between lanes lane ^ 1 .. lane ^ (rot / 16).  Every lane of
+// the wavefront must call it (the exchanges are wavefront-wide); rot = 0 returns the weights.
+__device__ inline void load8_rotated(const float *wrow, int64_t k8, int64_t K, bool live, int rot,
+                                     int lane, float (&v)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (live && k8 + e < K) ? wrow[k8 + e] : 0.0f;
+    if (rot == 0) return;
+#pragma unroll
+    for (int h = 1; h < 8; h <<= 1)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if ((j & h) == 0) {
+                const float lo = v[j], hi = v[j + h];
+                v[j] = lo + hi;
+                v[j + h] = lo - hi;
+            }
+    for (int h = 8; h < rot; h <<= 1) {
+        const int partner = h >> 3;
+        const float sign = (lane & partner) ? -1.0f : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = fmaf(sign, v[e], __shfl_xor(v[e], partner));
+    }
+    const float inv = 1.0f / (float)rot;  // a power of two: exact
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= inv;
+}
+
 // One wavefront per (padded) output channel.
 __global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__restrict__ W,
                                                                int64_t N, int64_t K, int bits,
+                                                               int rot,
                                                                uint8_t *__restrict__ blob,
                                                                float *__restrict__ w_scale,
                                                                int64_t Np, int64_t Kp) {
@@ -38,15 +70,22 @@ __global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__re
         h32[1] = (uint32_t)bits;
         int64_t *h64 = reinterpret_cast<int64_t *>(blob + 8);
         h64[0] = N; h64[1] = K; h64[2] = Np; h64[3] = Kp;
+        h32[10] = (uint32_t)rot;
     }
     if (n >= Np) return;
     const bool live = n < N;
     const float *wrow = W + (live ? n : 0) * K;
     const float qmax = bits == 8 ? 127.0f : 7.0f;
 
+    // the same trip count for every lane: the rotation exchanges values across the wavefront
+    const int64_t trips = (Kp + 64 * 8 - 1) / (64 * 8);
     float a = 0.0f;
-    if (live)
-        for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(wrow[k]));
+    for (int64_t t = 0; t < trips; ++t) {
+        float v[8];
+        load8_rotated(wrow, (t * 64 + lane) * 8, K, live, rot, lane, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(v[e]));
+    }
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
     const float s = fmaxf(a, kAbsmaxFloor) / qmax;
@@ -55,11 +94,15 @@ __global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__re
     uint8_t *codes = blob + kPackedHeaderBytes;
     const int64_t KF = Kp / kFragK;
     const int64_t p = weight_row_of_channel(n);
-    for (int64_t k8 = (int64_t)lane * 8; k8 < Kp; k8 += 64 * 8) {
+    for (int64_t t = 0; t < trips; ++t) {
+        const int64_t k8 = (t * 64 + lane) * 8;
+        float v[8];
+        load8_rotated(wrow, k8, K, live, rot, lane, v);
+        if (k8 >= Kp) continue;
         int c[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            c[e] = (live && k8 + e < K) ? weight_code(wrow[k8 + e], s, qmax) : 0;
+            c[e] = (live && k8 + e < K) ? weight_code(v[e], s, qmax) : 0;
         if (bits == 8) {
             uint2 out;
             out.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | ((uint32_t)(c[3] & 0xff) << 24);
@@ -120,16 +163,30 @@ extern "C" size_t qc_packed_weight_bytes(int64_t N, int64_t K, int bits) {
     return (size_t)kPackedHeaderBytes + (size_t)(Np * Kp * bits / 8);
 }
 
-extern "C" qc_status qc_pack_weight(const float *W, int64_t N, int64_t K, int bits, void *packed,
-                                    float *w_scale, void *stream) {
+namespace {
+qc_status pack_weight_any(const float *W, int64_t N, int64_t K, int bits, int rot, void *packed,
+                          float *w_scale, void *stream) {
     if (!W || !packed || !w_scale || N < 1 || K < 1) return QC_ERR_INVALID_ARG;
     if (!aligned(W, 16) || !aligned(packed, 256) || !aligned(w_scale, 16)) return QC_ERR_INVALID_ARG;
     if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    if (rot && !quant_rotation_supported(K, rot)) return QC_ERR_UNSUPPORTED;
     const int64_t Np = round_up(N, kTileN), Kp = round_up(K, kKAlign);
     const int64_t blocks = Np / (kThreads / 64);
     pack_weight_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
-        W, N, K, bits, (uint8_t *)packed, w_scale, Np, Kp);
+        W, N, K, bits, rot, (uint8_t *)packed, w_scale, Np, Kp);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+}  // namespace
+
+extern "C" qc_status qc_pack_weight(const float *W, int64_t N, int64_t K, int bits, void *packed,
+                                    float *w_scale, void *stream) {
+    return pack_weight_any(W, N, K, bits, 0, packed, w_scale, stream);
+}
+
+extern "C" qc_status qc_pack_weight_rot(const float *W, int64_t N, int64_t K, int bits,
+                                        int rot_block, void *packed, float *w_scale, void *stream) {
+    if (rot_block == 0) return QC_ERR_UNSUPPORTED;
+    return pack_weight_any(W, N, K, bits, rot_block, packed, w_scale, stream);
 }
 
 extern "C" qc_status qc_unpack_weight_codes(const void *packed, int64_t N, int64_t K, int bits,

@@ -161,6 +161,115 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     }
 }
 
+// ---- rotation fused into the quantization (Section 3.2 AIGQ (1); Section 4.1 "Hardware
+// Implementation") -----------------------------------------------------------------------------
+// Each block of `rot` consecutive columns (16, 32, 64 or 128) is multiplied by the Walsh-Hadamard
+// matrix of that size before the absmax and the cast, as a butterfly network in binary32 with
+// the strides in ascending order: one rounding per output and stage, so the bits do not depend
+// on which lane does which butterfly.  With the lane layout above, the 8 lanes of a row hold one
+// aligned run of 128 columns per register unit: strides 1..8 are butterflies inside a lane's 16
+// values, strides 16, 32, 64 pair lanes sub ^ 1, sub ^ 2, sub ^ 4 (DPP moves, no LDS).
+
+__device__ inline float dpp_quad_xor1(float v) {  // lane ^ 1: quad_perm [1, 0, 3, 2]
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));
+}
+__device__ inline float dpp_quad_xor2(float v) {  // lane ^ 2: quad_perm [2, 3, 0, 1]
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));
+}
+__device__ inline float dpp_xor4(float v) {
+    // lanes 0-3 and 8-11 of a row of 16 take lane + 4 (row_shl:4, banks 0 and 2), the others
+    // lane - 4 (row_shr:4, banks 1 and 3)
+    int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x104, 0xF, 0x5, false);
+    t = __builtin_amdgcn_update_dpp(t, __float_as_int(v), 0x114, 0xF, 0xA, false);
+    return __int_as_float(t);
+}
+
+template <typename XT>
+__global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
+    const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax, int rot) {
+    __shared__ float slice_max[kMaxSlices][kRowsPerBlock];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6, slices = blockDim.x >> 6;
+    const int sub = lane % kLanesPerRow, row_in_block = lane / kLanesPerRow;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + row_in_block;
+    const int units = (int)(K / kUnit);
+    const bool live = row < M;
+    const XT *xrow = X + (live ? row : 0) * K;
+
+    Unit<XT> u[kUnitsPerThread];
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
+        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        else u[i].zero();
+    }
+
+    // +1 for the lane that holds the lower half of a cross-lane pair, -1 for the upper one:
+    // fma(sign, own, other) is own + other below and other - own above, one rounding either way
+    const float sg1 = (sub & 1) ? -1.0f : 1.0f, sg2 = (sub & 2) ? -1.0f : 1.0f,
+                sg4 = (sub & 4) ? -1.0f : 1.0f;
+    float f[kUnitsPerThread][kUnit];
+    float a = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e) f[i][e] = u[i].get(e);
+#pragma unroll
+        for (int h = 1; h < kUnit; h <<= 1)
+#pragma unroll
+            for (int j = 0; j < kUnit; ++j)
+                if ((j & h) == 0) {
+                    const float lo = f[i][j], hi = f[i][j + h];
+                    f[i][j] = lo + hi;
+                    f[i][j + h] = lo - hi;
+                }
+        if (rot >= 32) {
+#pragma unroll
+            for (int e = 0; e < kUnit; ++e) f[i][e] = fmaf(sg1, f[i][e], dpp_quad_xor1(f[i][e]));
+        }
+        if (rot >= 64) {
+#pragma unroll
+            for (int e = 0; e < kUnit; ++e) f[i][e] = fmaf(sg2, f[i][e], dpp_quad_xor2(f[i][e]));
+        }
+        if (rot >= 128) {
+#pragma unroll
+            for (int e = 0; e < kUnit; ++e) f[i][e] = fmaf(sg4, f[i][e], dpp_xor4(f[i][e]));
+        }
+#pragma unroll
+        for (int e = 0; e < kUnit; ++e) a = fmaxf(a, fabsf(f[i][e]));
+    }
+#pragma unroll
+    for (int d = 1; d < kLanesPerRow; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    if (slices > 1) {  // uniform over the block
+        if (sub == 0) slice_max[slice][row_in_block] = a;
+        __syncthreads();
+        for (int sl = 0; sl < slices; ++sl) a = fmaxf(a, slice_max[sl][row_in_block]);
+    }
+
+    const float s = scale_of(a, qmax);
+    const float r = 1.0f / s;  // correctly rounded
+    if (live && sub == 0 && slice == 0) x_scale[row] = s;
+    if (!live) return;
+
+    int8_t *out_rows = qx ? qx + row * K : nullptr;
+    uint8_t *out_tiled = qx_tiled ? qx_tiled + (row / kFragRows) * KF * kFragBytes + (row % kFragRows) * 16
+                                  : nullptr;
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
+        if (ui >= units) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            w[d] = codes4(quotient(f[i][4 * d + 0], s, r), quotient(f[i][4 * d + 1], s, r),
+                          quotient(f[i][4 * d + 2], s, r), quotient(f[i][4 * d + 3], s, r), qmax);
+        const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
+        if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
+        if (out_tiled)
+            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 1) * kFragBytes + (ui & 1) * 512) = out;
+    }
+}
+
 // Any K, any alignment: one wavefront per row, two passes over the row (the second one is
 // served by the caches).  Slow path for shapes the vector kernel does not take.
 template <typename XT>
@@ -190,10 +299,17 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
 
 template <typename XT>
 hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
-                        int64_t KF, float *x_scale, float qmax, hipStream_t stream) {
+                        int64_t KF, float *x_scale, float qmax, int rot, hipStream_t stream) {
     const int64_t units = K / kUnit;
     const int64_t slices = (units + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const bool vec = (K % kUnit == 0) && slices <= kMaxSlices;
+    if (rot) {
+        if (!vec || K % rot) return hipErrorInvalidValue;  // the entry points reject these first
+        const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
+        quant_rows_rot_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+            X, M, K, qx, qx_tiled, KF, x_scale, qmax, rot);
+        return hipGetLastError();
+    }
     if (!vec) {
         const int64_t blocks = (M + 3) / 4;
         quant_rows_generic_kernel<XT><<<dim3((unsigned)blocks), dim3(kGenericThreads), 0, stream>>>(
@@ -208,15 +324,20 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
 
 }  // namespace
 
+bool quant_rotation_supported(int64_t K, int rot_block) {
+    if (rot_block != 16 && rot_block != 32 && rot_block != 64 && rot_block != 128) return false;
+    return K % rot_block == 0 && K / kUnit <= (int64_t)kUnitsPerSlice * kMaxSlices;
+}
+
 hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx_rowmajor,
                             uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
-                            hipStream_t stream) {
+                            int rot_block, hipStream_t stream) {
     const float qmax = (float)((1 << (act_bits - 1)) - 1);  // 127, 31 or 7 in an int8 container
     if (xdt == QC_BF16)
         return launch_typed<uint16_t>((const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale,
-                                      qmax, stream);
+                                      qmax, rot_block, stream);
     return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, qmax,
-                               stream);
+                               rot_block, stream);
 }
 
 }  // namespace qc

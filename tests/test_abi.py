@@ -85,6 +85,21 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_layer_similarity(A, A, 5, 8, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_layer_similarity(A, A, qc.QC_BF16, 8, A, A, 8) == qc.QC_ERR_WORKSPACE
     assert qc.qc_layer_similarity_workspace_bytes(100) == 256 * 24
+    # rotation: block sizes, divisibility, the K limit of the vector path
+    assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 0, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 48, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 256, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1000, 8, 64, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 9216 + 128, 8, 128, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_rot(None, qc.QC_BF16, 4, 1152, 8, 128, A, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_pack_weight_rot(A, 8, 1152, 8, 100, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_pack_weight_rot(A, 8, 1152, 8, 128, None, A) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_qlinear_quant_rot(A, qc.QC_BF16, 4, 1152, 8, 128, A, 16) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_qlinear_quant_rot(A, qc.QC_BF16, 4, 1152, 8, 8, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_qlinear_rot(A, qc.QC_BF16, 4, 1152, 8, 96, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
+                             qc.QC_OUT_BF16, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_qlinear_rot(A, qc.QC_BF16, 4, 1152, 8, 128, A, A, 8, 8, None, qc.QC_EPI_NONE, None,
+                             qc.QC_OUT_BF16, A, 1 << 30) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_frame_gradient_norm(None, qc.QC_F32, 4, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_frame_gradient_norm(A, qc.QC_F32, 0, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG
     assert qc.qc_frame_gradient_norm(A, 5, 4, 16, A, A, 1 << 20) == qc.QC_ERR_INVALID_ARG

@@ -133,21 +133,26 @@ def test_pack_int4_all_nibbles_all_positions():
 
 # ------------------------------------------------------------------ qc_qlinear
 
-def run_linear_case(x, W, b, bits, epi, out, check_acc=True, act_bits=8):
+def run_linear_case(x, W, b, bits, epi, out, check_acc=True, act_bits=8, rot_block=0):
     M, K = x.shape
     N = W.shape[0]
-    qw_ref, sw_ref = oracle.quant_weight(W, bits)
-    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi], act_bits)
-    xd, pw = dev(x), qc.pack_weight_t(dev(W), bits)
+    if rot_block:
+        qw_ref, sw_ref = oracle.quant_weight_rot(W, bits, rot_block)
+        ref = oracle.qlinear_rot(x, qw_ref, sw_ref, rot_block, b, EPI_ORACLE[epi], act_bits)
+    else:
+        qw_ref, sw_ref = oracle.quant_weight(W, bits)
+        ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi], act_bits)
+    xd, pw = dev(x), qc.pack_weight_t(dev(W), bits, rot_block)
     bd = None if b is None else dev(b)
     ws = qc.qlinear_workspace_t(M, K, N)
-    y = qc.qlinear_t(xd, pw, bd, epi, out, workspace=ws, act_bits=act_bits)
+    y = qc.qlinear_t(xd, pw, bd, epi, out, workspace=ws, act_bits=act_bits, rot_block=rot_block)
     qx, sx = qc.debug_workspace_act_t(ws, M, K)
     torch.cuda.synchronize()
     assert bits_equal(sx.cpu().numpy(), ref["sx"]), "activation scales differ"
     assert np.array_equal(qx.cpu().numpy(), ref["qx"]), "activation codes differ"
     if check_acc:
-        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws, act_bits=act_bits)
+        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws, act_bits=act_bits,
+                           rot_block=rot_block)
         torch.cuda.synchronize()
         assert np.array_equal(acc.cpu().numpy(), ref["acc"]), "int32 accumulators differ"
     y_ref = ref["y"]
@@ -407,3 +412,71 @@ def test_cumulative_variation_agrees_with_latent_delta_and_closed_forms():
     one = qc.cumulative_variation_t(a, [b]).cpu().numpy()
     pair = qc.latent_delta_t(a, b).cpu().numpy()
     assert abs(one[0] - pair[0]) <= 1e-6 * pair[0] and one[1] == one[0]
+
+
+# ------------------------------------------------------------------ rotation fused into quantization
+
+@pytest.mark.parametrize("rot_block", [16, 32, 64, 128])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K,act_bits", [(256, 1152, 8), (77, 4608, 6), (9, 128, 8), (33, 9216, 4),
+                                          (5, 2304, 8), (1, 640, 8)])
+def test_quant_act_rot_bit_exact(rot_block, dtype, M, K, act_bits):
+    rng = np.random.default_rng(M * 1009 + K + rot_block)
+    x = random_x(rng, M, K, dtype)
+    q_ref, s_ref = oracle.quant_act_rot(x, rot_block, act_bits)
+    qx, sx = qc.quant_act_t(dev(x), act_bits, rot_block)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), s_ref)
+    assert np.array_equal(qx.cpu().numpy(), q_ref)
+
+
+@pytest.mark.parametrize("rot_block", [16, 64, 128])
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K", [(1152, 1152), (200, 128), (3, 640), (129, 4608)])
+def test_pack_weight_rot_codes_and_scales_bit_exact(rot_block, bits, N, K):
+    rng = np.random.default_rng(N * 7919 + K + bits + rot_block)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    W[N // 2] = 0
+    q_ref, s_ref = oracle.quant_weight_rot(W, bits, rot_block)
+    pw = qc.pack_weight_t(dev(W), bits, rot_block)
+    codes = qc.unpack_weight_codes_t(pw)
+    torch.cuda.synchronize()
+    assert bits_equal(pw.scale.cpu().numpy(), s_ref)
+    assert np.array_equal(codes.cpu().numpy(), q_ref)
+
+
+@pytest.mark.parametrize("bits,act_bits,rot_block", [(8, 8, 128), (4, 8, 128), (4, 6, 64), (8, 4, 16)])
+def test_qlinear_rot_matches_oracle(bits, act_bits, rot_block):
+    rng = np.random.default_rng(bits * 100 + act_bits * 10 + rot_block)
+    M, K, N = 520, 1152, 300
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_linear_case(x, W, b, bits, "gelu_tanh", "bf16", act_bits=act_bits, rot_block=rot_block)
+    run_linear_case(x, W, b, bits, "none", "f32", act_bits=act_bits, rot_block=rot_block)
+
+
+def test_qlinear_rot_leaves_the_product_and_cuts_outlier_error():
+    """(X H)(W H / b)^T = X W^T: with outlier channels the rotated W4A8 linear is closer to the
+    exact product than the plain one, and on integers both are exact."""
+    rng = np.random.default_rng(2024)
+    M, K, N = 512, 1152, 256
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    exact = oracle.bf16_bits_to_f64(x) @ W.astype(np.float64).T
+    xd = dev(x)
+    err = {}
+    for rot in (0, 128):
+        pw = qc.pack_weight_t(dev(W), 4, rot)
+        y = host_f64(qc.qlinear_t(xd, pw, None, "none", "f32", rot_block=rot))
+        err[rot] = math.sqrt(float(np.mean((y - exact) ** 2)) / float(np.mean(exact ** 2)))
+    assert err[128] < err[0] and err[128] < 0.2, err
+    # integer operands whose rotated images stay on the code grid: every step is exact
+    xi = np.zeros((256, 256), np.float32)
+    xi[np.arange(256), np.arange(256)] = 127.0            # rows of 127 * identity
+    wi = np.zeros((128, 256), np.float32)
+    wi[np.arange(128), np.arange(128) * 2] = 7.0
+    pw = qc.pack_weight_t(dev(wi), 8, 128)
+    y = host_f64(qc.qlinear_t(dev(xi), pw, None, "none", "f32", rot_block=128))
+    want = xi.astype(np.float64) @ wi.astype(np.float64).T
+    assert np.max(np.abs(y - want)) <= 1e-3 * 889
