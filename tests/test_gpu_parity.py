@@ -227,6 +227,22 @@ def test_qlinear_closed_form_integers_and_extremes():
         assert np.allclose(y, ref + b, rtol=3e-7, atol=0)
 
 
+def test_qlinear_largest_reduction_length():
+    """K = QC_MAX_K: all-127 operands reach 127 * 127 * K = 2 114 060 288 < 2^31 without
+    wrapping; random rows agree with an int64 product."""
+    K, M, N = qc.QC_MAX_K, 33, 130
+    rng = np.random.default_rng(13)
+    X = rng.integers(-127, 128, size=(M, K)).astype(np.float32)
+    W = rng.integers(-127, 128, size=(N, K)).astype(np.float32)
+    X[:, 0], W[:, 1] = 127, 127
+    X[0], W[0], X[1] = 127, 127, -127
+    pw = qc.pack_weight_t(dev(W), 8)
+    acc = qc.qlinear_t(dev(X), pw, None, "none", "i32").cpu().numpy()
+    assert np.array_equal(acc.astype(np.int64), X.astype(np.int64) @ W.astype(np.int64).T)
+    assert acc[0, 0] == 127 * 127 * K and acc[1, 0] == -127 * 127 * K
+    assert qc.qc_qlinear_workspace_bytes(M, K + 1, N) == 0
+
+
 def test_qlinear_one_hot_rows_return_weight_columns():
     K, N = 128, 256
     rng = np.random.default_rng(9)
