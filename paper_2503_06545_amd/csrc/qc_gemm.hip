@@ -19,6 +19,8 @@
 // read again by this kernel and would otherwise push the operand panels out of the L2.
 #include <type_traits>
 
+#include <atomic>
+
 #include "qc_internal.h"
 
 namespace qc {
@@ -379,12 +381,17 @@ template <int BITS, int OUT, int EPI>
 hipError_t launch_variant(const GemmArgs &args, hipStream_t stream) {
     using L = StageLayout<BITS>;
     constexpr int kLds = kStages * L::kBytes + (kTileM + 2 * kTileN) * (int)sizeof(float);
-    static bool configured = false;  // a per-function attribute; setting it twice is harmless
-    if (!configured) {
+    // The attribute belongs to the function on one device: set it once per device (setting it
+    // twice, as two threads racing here may, is harmless).
+    static std::atomic<uint64_t> configured{0};
+    int device = 0;
+    if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (device & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, OUT, EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.fetch_or(bit, std::memory_order_release);
     }
     const int blocks = args.m_tiles * args.n_tiles;
     gemm_kernel<BITS, OUT, EPI><<<dim3((unsigned)blocks), dim3(kThreads), kLds, stream>>>(args);
