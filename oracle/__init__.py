@@ -15,6 +15,8 @@ Paper passages each function follows (arxiv 2503.06545):
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
   layer_similarity          Section 3.3 SRAP, Eq. (9)
+  quant_act_asym,           Section 3.1 Eq. (3), Eq. (4) as printed: asymmetric, with a zero
+  qlinear_asym              point per token
   rotate_rows, quant_act_   Section 3.2 AIGQ (1) (rotation against outlier channels) and
   rot, quant_weight_rot,    Section 4.1 "Hardware Implementation" (rotation fused with the
   qlinear_rot               quantization), as a block Walsh-Hadamard transform over K
@@ -72,6 +74,10 @@ def _L():
         lib.orc_latent_delta.argtypes = [vp, vp, i64, vp]
         lib.orc_layer_similarity.argtypes = [vp, vp, i32, i64, vp]
         lib.orc_layer_similarity.restype = None
+        lib.orc_quant_rows_asym.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp]
+        lib.orc_quant_rows_asym.restype = None
+        lib.orc_qlinear_asym.argtypes = [vp, i32, i64, i64, i32, vp, vp, i64, vp, i32, vp, vp, vp, vp]
+        lib.orc_qlinear_asym.restype = None
         lib.orc_rotate_rows_f32.argtypes = [vp, i64, i64, i32, ctypes.c_float, vp]
         lib.orc_rotate_rows_f32.restype = None
         lib.orc_frame_gradient.argtypes = [vp, i32, i64, i64, vp]
@@ -336,3 +342,41 @@ def quant_weight_rot(W, bits: int, block: int):
 def qlinear_rot(X, qw, sw, block: int, bias=None, epi=EPI_NONE, act_bits: int = 8):
     """The quantized linear on rotated activations; qw / sw come from quant_weight_rot."""
     return qlinear(rotate_rows(widen_f32(X), block), qw, sw, bias, epi, act_bits)
+
+
+# ---- the printed, asymmetric form of the activation quantizer ---------------------------------
+
+def levels(bits: int) -> int:
+    """Largest code of the b-bit unsigned quantizer of Eq. (3): 2^b - 1."""
+    return (1 << bits) - 1
+
+
+def quant_act_asym(X, act_bits: int = 8):
+    """Per-token asymmetric quantization: (uint8 codes in [0, 2^b - 1], float32 scales,
+    float32 integer-valued zero points); dequantized value = s * (code - z)."""
+    is_bf16 = X.dtype == np.uint16
+    X = _c(X, np.uint16 if is_bf16 else np.float32)
+    R, K = X.shape
+    q = np.empty((R, K), np.uint8)
+    s = np.empty((R,), np.float32)
+    z = np.empty((R,), np.float32)
+    _L().orc_quant_rows_asym(_p(X), int(is_bf16), R, K, levels(act_bits), _p(q), _p(s), _p(z))
+    return q, s, z
+
+
+def qlinear_asym(X, qw, sw, bias=None, epi=EPI_NONE, act_bits: int = 8):
+    """Quantized linear with asymmetric activations; returns dict(qx, sx, zx, y), y float64."""
+    is_bf16 = X.dtype == np.uint16
+    X = _c(X, np.uint16 if is_bf16 else np.float32)
+    qw, sw = _c(qw, np.int8), _c(sw, np.float32)
+    bias = None if bias is None else _c(bias, np.float32)
+    M, K = X.shape
+    N = qw.shape[0]
+    assert qw.shape[1] == K and sw.shape[0] == N
+    qx = np.empty((M, K), np.uint8)
+    sx = np.empty((M,), np.float32)
+    zx = np.empty((M,), np.float32)
+    y = np.empty((M, N), np.float64)
+    _L().orc_qlinear_asym(_p(X), int(is_bf16), M, K, levels(act_bits), _p(qw), _p(sw), N,
+                          _p(bias), int(epi), _p(qx), _p(sx), _p(zx), _p(y))
+    return {"qx": qx, "sx": sx, "zx": zx, "y": y}

@@ -10,7 +10,9 @@
  *   - uniform quantizer, Section 3.1 "Model Quantization", Eq. (3) and Eq. (4)
  *     (third and fourth displayed equations), taken in its symmetric signed
  *     form: range [-a, +a], 2^b - 1 levels, zero point at mid range, so the
- *     stored code is rne(x / s) with s = a / (2^(b-1) - 1);
+ *     stored code is rne(x / s) with s = a / (2^(b-1) - 1); and, for
+ *     activations, also as printed (orc_quant_rows_asym): unsigned codes with
+ *     a zero point per token, s = (max - min) / (2^b - 1);
  *   - Section 4.1 "Quantization Scheme": one scale per output channel of a
  *     weight, activation scales computed online (here: one per token row);
  *   - Section 3.2 AIGQ (1): the weight bit-width is chosen per layer, so the
@@ -359,4 +361,78 @@ void orc_rotate_rows_f32(const float *X, int64_t R, int64_t K, int block, float 
             }
         }
     }
+}
+
+/*
+ * The quantizer of Section 3.1 in its printed, asymmetric form, one row (a token):
+ *   Eq. (4):  s = (max(x) - min(x)) / (2^b - 1)
+ *   Eq. (3):  x_int = clamp(rne(x / s) + z, 0, 2^b - 1)
+ * The paper does not print z; the usual choice that sends min(x) to code 0 is taken:
+ *   z = -rne(min(x) / s),   dequantized value  s * (x_int - z).
+ * levels = 2^b - 1 (255, 63 or 15).  Steps, each one binary32 operation [bit]:
+ *   range = hi - lo;  s = max(range, 2^-64) / levels;  z = -rne(lo / s);
+ *   x_int = clamp(rne(x / s) + z, 0, levels)   (the sum of two integer-valued floats)
+ * z is kept as an integer-valued float: for a row far from zero with a narrow range it
+ * exceeds every integer type that would be natural here.
+ */
+static void quant_row_asym(const float *x, int64_t K, int levels, uint8_t *q, float *s_out,
+                           float *z_out) {
+    float lo = x[0], hi = x[0];
+    for (int64_t k = 1; k < K; ++k) {
+        if (x[k] < lo) lo = x[k];
+        if (x[k] > hi) hi = x[k];
+    }
+    float range = hi - lo;
+    float floored = range > ORC_ABSMAX_FLOOR ? range : ORC_ABSMAX_FLOOR;
+    float s = floored / (float)levels;
+    float lo_over_s = lo / s;
+    float z = -rintf(lo_over_s);
+    for (int64_t k = 0; k < K; ++k) {
+        float t = x[k] / s;
+        float v = rintf(t) + z;
+        if (v < 0.0f) v = 0.0f;
+        if (v > (float)levels) v = (float)levels;
+        q[k] = (uint8_t)v;
+    }
+    *s_out = s;
+    *z_out = z;
+}
+
+void orc_quant_rows_asym(const void *X, int x_is_bf16, int64_t R, int64_t K, int levels,
+                         uint8_t *q, float *s, float *z) {
+#pragma omp parallel
+    {
+        float *tmp = (float *)malloc((size_t)(K > 0 ? K : 1) * sizeof(float));
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < R; ++r) {
+            for (int64_t k = 0; k < K; ++k)
+                tmp[k] = x_is_bf16 ? bf16_bits_to_f32(((const uint16_t *)X)[r * K + k])
+                                   : ((const float *)X)[r * K + k];
+            quant_row_asym(tmp, K, levels, q + r * K, s + r, z + r);
+        }
+        free(tmp);
+    }
+}
+
+/*
+ * The linear layer on asymmetric activation codes and symmetric weight codes, written as the
+ * product of the dequantized operands:
+ *   y[m, n] = act( sx[m] * sw[n] * sum_k (qx[m, k] - z[m]) * qw[n, k]  + bias[n] )
+ * The sum is exact in binary64 (integer-valued terms far below 2^53 for any sane row).
+ */
+void orc_qlinear_asym(const void *X, int x_is_bf16, int64_t M, int64_t K, int levels,
+                      const int8_t *qw, const float *sw, int64_t N, const float *bias, int epi,
+                      uint8_t *qx, float *sx, float *zx, double *y) {
+    orc_quant_rows_asym(X, x_is_bf16, M, K, levels, qx, sx, zx);
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double a = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                a += ((double)qx[m * K + k] - (double)zx[m]) * (double)qw[n * K + k];
+            double v = a * (double)sx[m] * (double)sw[n] + (bias ? (double)bias[n] : 0.0);
+            if (epi == ORC_EPI_GELU_TANH) v = gelu_tanh(v);
+            else if (epi == ORC_EPI_GELU_ERF) v = gelu_erf(v);
+            y[m * N + n] = v;
+        }
 }

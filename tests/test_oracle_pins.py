@@ -562,3 +562,98 @@ def test_rotation_leaves_the_linear_unchanged_and_spreads_outliers():
     q2, s2 = oracle.quant_act(oracle.rotate_rows(oracle.widen_f32(Xb), block), 6)
     assert np.array_equal(q1, q2) and np.array_equal(s1, s2)
     assert np.array_equal(oracle.widen_f32(Xb).astype(np.float64), oracle.bf16_bits_to_f64(Xb))
+
+
+# ------------------------------------------- the printed, asymmetric activation quantizer
+
+def exact_quant_row_asym(x: np.ndarray, levels: int):
+    """Eq. (3)/(4) as printed, every binary32 step redone in exact rational arithmetic."""
+    lo, hi = Fraction(float(x.min())), Fraction(float(x.max()))
+    rng = Fraction(round_fraction_to_f32(hi - lo))
+    rng = max(rng, Fraction(2) ** -64)
+    s = Fraction(round_fraction_to_f32(rng / levels))
+    z = -rne_int(Fraction(round_fraction_to_f32(lo / s)))
+    codes = [min(max(rne_int(Fraction(round_fraction_to_f32(Fraction(float(v)) / s))) + z, 0), levels)
+             for v in x]
+    return np.array(codes, np.int64), float(s), z
+
+
+@pytest.mark.parametrize("bits", [8, 6, 4])
+def test_asymmetric_quantizer_against_exact_rational_brute_force(bits):
+    rng = np.random.default_rng(83 + bits)
+    L = oracle.levels(bits)
+    rows = [rng.standard_normal(97).astype(np.float32),
+            (rng.standard_normal(97) + 5.0).astype(np.float32),            # all positive
+            (-np.abs(rng.standard_normal(97)) * 1e-3).astype(np.float32),   # all negative, small
+            np.maximum(rng.standard_normal(97), -0.17).astype(np.float32),  # one-sided, like GELU
+            (rng.standard_normal(97) * 1e4 + 3e4).astype(np.float32)]
+    X = np.stack(rows)
+    q, s, z = oracle.quant_act_asym(X, bits)
+    for r in range(X.shape[0]):
+        cq, cs, cz = exact_quant_row_asym(X[r], L)
+        assert np.array_equal(q[r].astype(np.int64), cq) and float(s[r]) == cs and float(z[r]) == cz
+        assert q[r].min() == 0 and q[r].max() == L        # the range is used end to end
+        # half-step invariant of the dequantized values (z is not clamped, so it holds at both ends)
+        back = float(s[r]) * (q[r].astype(np.float64) - float(z[r]))
+        assert np.max(np.abs(back - X[r])) <= 0.5 * float(s[r]) * (1 + 1e-5)
+
+
+def test_asymmetric_quantizer_closed_forms():
+    ramp = np.arange(256, dtype=np.float32)[None, :]
+    for shift, zero in ((0.0, 0.0), (-128.0, 128.0), (-255.0, 255.0), (1000.0, -1000.0)):
+        q, s, z = oracle.quant_act_asym(ramp + np.float32(shift))
+        assert s[0] == 1.0 and z[0] == zero and np.array_equal(q[0], np.arange(256))
+    # scale and shift equivariance on exactly representable values
+    q, s, z = oracle.quant_act_asym((ramp - 128) * np.float32(0.25))
+    assert s[0] == 0.25 and z[0] == 128.0 and np.array_equal(q[0], np.arange(256))
+    # 6 and 4 bits: 63 and 15 levels
+    for bits in (6, 4):
+        L = oracle.levels(bits)
+        q, s, z = oracle.quant_act_asym(np.arange(L + 1, dtype=np.float32)[None, :] - 3, bits)
+        assert s[0] == 1.0 and z[0] == 3.0 and np.array_equal(q[0], np.arange(L + 1))
+    # a constant row: the range floor keeps s positive, every code is 0 and the value survives
+    q, s, z = oracle.quant_act_asym(np.full((1, 16), 2.5, np.float32))
+    assert s[0] > 0 and not q.any() and abs(float(s[0]) * (0 - float(z[0])) - 2.5) < 1e-6
+    q, s, z = oracle.quant_act_asym(np.zeros((1, 16), np.float32))
+    assert not q.any() and z[0] == 0.0
+    # ties go to even before the zero point is added: x / s = 0.5, 1.5, 2.5 with s = 1
+    x = np.array([[0.0, 0.5, 1.5, 2.5, 255.0]], np.float32)
+    assert oracle.quant_act_asym(x)[0][0].tolist() == [0, 0, 2, 2, 255]
+    # bf16 input is widened exactly
+    from paper_2503_06545_amd import synth
+    xb = synth.to_bf16_bits(np.random.default_rng(5).standard_normal((3, 64)).astype(np.float32))
+    a = oracle.quant_act_asym(xb)
+    b = oracle.quant_act_asym(oracle.widen_f32(xb))
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+
+
+def test_asymmetric_linear_is_the_product_of_dequantized_operands_and_gains_a_bit_on_one_sided_rows():
+    rng = np.random.default_rng(89)
+    M, K, N = 12, 320, 20
+    # post-GELU-like activations: bounded below near -0.17, long tail above
+    g = rng.standard_normal((M, K))
+    X = (0.5 * g * (1 + np.tanh(0.7978845608 * (g + 0.044715 * g ** 3)))).astype(np.float32)
+    W = (0.02 * rng.standard_normal((N, K))).astype(np.float32)
+    b = (0.01 * rng.standard_normal(N)).astype(np.float32)
+    qw, sw = oracle.quant_weight(W, 8)
+    for bits in (8, 4):
+        r = oracle.qlinear_asym(X, qw, sw, b, oracle.EPI_NONE, bits)
+        xhat = r["sx"].astype(np.float64)[:, None] * (r["qx"].astype(np.float64) - r["zx"].astype(np.float64)[:, None])
+        what = sw.astype(np.float64)[:, None] * qw.astype(np.float64)
+        assert np.allclose(r["y"], xhat @ what.T + b, rtol=1e-12, atol=1e-15)
+        exact = X.astype(np.float64) @ what.T + b
+        sym = oracle.qlinear(X, qw, sw, b, oracle.EPI_NONE, bits)["y"]
+        e_asym, e_sym = np.abs(r["y"] - exact).mean(), np.abs(sym - exact).mean()
+        assert e_asym < 0.7 * e_sym, (bits, e_asym, e_sym)    # about one bit finer steps
+    # integers: exact
+    Xi = rng.integers(0, 256, size=(M, K)).astype(np.float32)
+    Xi[:, 0], Xi[:, 1] = 0, 255
+    Wi = rng.integers(-127, 128, size=(N, K)).astype(np.float32)
+    Wi[:, 0] = 127
+    qwi, swi = oracle.quant_weight(Wi, 8)
+    r = oracle.qlinear_asym(Xi - 100, qwi, swi)
+    assert np.array_equal(r["y"], (Xi.astype(np.float64) - 100) @ Wi.astype(np.float64).T)
+    # and the GELU epilogue is applied after the bias
+    rg = oracle.qlinear_asym(X, qw, sw, b, oracle.EPI_GELU_ERF)["y"]
+    rn = oracle.qlinear_asym(X, qw, sw, b, oracle.EPI_NONE)["y"]
+    assert np.allclose(rg, [[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row] for row in rn], rtol=1e-12, atol=1e-15)
