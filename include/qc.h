@@ -184,6 +184,45 @@ qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int 
                          int64_t N, const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- asymmetric activation quantization ---------------------------------------------------
+ * Section 3.1, Eq. (3) and Eq. (4) as printed: unsigned codes with a zero point, here one scale
+ * and one zero point per token.  With levels = 2^act_bits - 1 (255, 63, 15), lo / hi the
+ * minimum / maximum of the token's row, every step one IEEE binary32 operation:
+ *      s = max(hi - lo, 2^-64) / levels
+ *      z = -rne(lo / s)                              (the zero point the paper leaves open:
+ *                                                     the row minimum gets code 0)
+ *      q = clamp(rne(x / s) + z, 0, levels)          dequantized value  s * (q - z)
+ * Weights stay symmetric, so
+ *      Y[m, n] = act( s[m] w_scale[n] * sum_k (q[m, k] - z[m]) qw[n, k] + bias[n] ).
+ * The GEMM runs on the signed bytes q - 2^(act_bits-1); the epilogue adds
+ * (2^(act_bits-1) - z[m]) * w_row_sums[n] in binary32.  One-sided inputs (the post-GELU input
+ * of the MLP's second linear) gain about one bit over the symmetric form.
+ *
+ *   qc_weight_row_sums   w_row_sums[n] = sum_k qw[n, k] (int32 [N], device, 16-byte aligned),
+ *                        computed once from a blob written by qc_pack_weight / _rot.
+ *   qc_quant_act_asym    stand-alone quantizer: qx uint8 [M, K] row major, x_scale float [M],
+ *                        x_zero float [M] (integer valued; a float because a row far from zero
+ *                        with a narrow range has a zero point beyond int32).
+ *   qc_qlinear_asym      quantize + GEMM + epilogue.  workspace >=
+ *                        qc_qlinear_asym_workspace_bytes(M, K, N) bytes.  With QC_OUT_I32_ACC, Y
+ *                        is sum_k (q[m, k] - 2^(act_bits-1)) qw[n, k], the sum the MFMA loop
+ *                        forms on the stored bytes.
+ *   qc_debug_workspace_act_asym   test hook: the codes, scales and zero points
+ *                        qc_qlinear_asym left in its workspace, in canonical form.
+ * act_bits 8, 6 or 4.  K must be a multiple of 16 and at most 9216 (UNSUPPORTED otherwise).
+ * Other arguments and errors as for qc_qlinear. */
+size_t qc_qlinear_asym_workspace_bytes(int64_t M, int64_t K, int64_t N);
+qc_status qc_weight_row_sums(const void *packed, int64_t N, int64_t K, int bits,
+                             int32_t *w_row_sums, void *stream);
+qc_status qc_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                            uint8_t *qx, float *x_scale, float *x_zero, void *stream);
+qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                          const void *packed, const float *w_scale, const int32_t *w_row_sums,
+                          int bits, int64_t N, const float *bias, qc_epilogue epi, void *Y,
+                          qc_out ydt, void *workspace, size_t workspace_bytes, void *stream);
+qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t M, int64_t K, int act_bits,
+                                      uint8_t *qx, float *x_scale, float *x_zero, void *stream);
+
 /* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
  * activation codes and scales it used out of the workspace in canonical order:
  * qx int8 [M, K] row major, x_scale float [M]. */

@@ -29,6 +29,8 @@ EXPORTS = (
     "qc_cumulative_variation_workspace_bytes", "qc_cumulative_variation",
     "qc_divergence_score", "qc_cache_interval", "qc_activation_bits", "qc_prune_probability",
     "qc_pack_weight_rot", "qc_quant_act_rot", "qc_qlinear_quant_rot", "qc_qlinear_rot",
+    "qc_qlinear_asym_workspace_bytes", "qc_weight_row_sums", "qc_quant_act_asym",
+    "qc_qlinear_asym", "qc_debug_workspace_act_asym",
 )
 
 
@@ -87,6 +89,17 @@ def lib() -> ctypes.CDLL:
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
         f32 = ctypes.c_float
+        L.qc_qlinear_asym_workspace_bytes.restype = sz
+        L.qc_qlinear_asym_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qc_weight_row_sums.restype = i32
+        L.qc_weight_row_sums.argtypes = [vp, i64, i64, i32, vp, vp]
+        L.qc_quant_act_asym.restype = i32
+        L.qc_quant_act_asym.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp, vp]
+        L.qc_qlinear_asym.restype = i32
+        L.qc_qlinear_asym.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp, i32, i64, vp, i32, vp, i32,
+                                      vp, sz, vp]
+        L.qc_debug_workspace_act_asym.restype = i32
+        L.qc_debug_workspace_act_asym.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.qc_pack_weight_rot.restype = i32
         L.qc_pack_weight_rot.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp]
         L.qc_quant_act_rot.restype = i32
@@ -217,6 +230,29 @@ def qc_qlinear_rot(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N, 
                    workspace, workspace_bytes, stream=0) -> int:
     return int(lib().qc_qlinear_rot(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N,
                                     bias, epi, Y, ydt, workspace, workspace_bytes, stream))
+
+
+def qc_qlinear_asym_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().qc_qlinear_asym_workspace_bytes(M, K, N))
+
+
+def qc_weight_row_sums(packed, N, K, bits, w_row_sums, stream=0) -> int:
+    return int(lib().qc_weight_row_sums(packed, N, K, bits, w_row_sums, stream))
+
+
+def qc_quant_act_asym(X, xdt, M, K, act_bits, qx, x_scale, x_zero, stream=0) -> int:
+    return int(lib().qc_quant_act_asym(X, xdt, M, K, act_bits, qx, x_scale, x_zero, stream))
+
+
+def qc_qlinear_asym(X, xdt, M, K, act_bits, packed, w_scale, w_row_sums, bits, N, bias, epi, Y, ydt,
+                    workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_asym(X, xdt, M, K, act_bits, packed, w_scale, w_row_sums, bits, N,
+                                     bias, epi, Y, ydt, workspace, workspace_bytes, stream))
+
+
+def qc_debug_workspace_act_asym(workspace, M, K, act_bits, qx, x_scale, x_zero, stream=0) -> int:
+    return int(lib().qc_debug_workspace_act_asym(workspace, M, K, act_bits, qx, x_scale, x_zero,
+                                                 stream))
 
 
 def qc_frame_gradient_norm_workspace_bytes(frames: int, inner: int) -> int:
@@ -444,3 +480,62 @@ def cumulative_variation_t(cur, prevs, workspace=None, out=None):
                                    _stream()),
            "qc_cumulative_variation")
     return out
+
+
+# ---- asymmetric activations ---------------------------------------------------------------------
+
+def weight_row_sums_t(pw: PackedWeight):
+    torch = _torch()
+    sums = torch.empty(pw.N, dtype=torch.int32, device=pw.blob.device)
+    _check(qc_weight_row_sums(pw.blob.data_ptr(), pw.N, pw.K, pw.bits, sums.data_ptr(), _stream()),
+           "qc_weight_row_sums")
+    return sums
+
+
+def quant_act_asym_t(X, act_bits: int = 8):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2
+    M, K = X.shape
+    qx = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    sx = torch.empty(M, dtype=torch.float32, device=X.device)
+    zx = torch.empty(M, dtype=torch.float32, device=X.device)
+    _check(qc_quant_act_asym(X.data_ptr(), _xdt(X), M, K, act_bits, qx.data_ptr(), sx.data_ptr(),
+                             zx.data_ptr(), _stream()), "qc_quant_act_asym")
+    return qx, sx, zx
+
+
+def qlinear_asym_workspace_t(M: int, K: int, N: int, device="cuda"):
+    torch = _torch()
+    nbytes = qc_qlinear_asym_workspace_bytes(M, K, N)
+    if nbytes == 0:
+        raise QcError(QC_ERR_UNSUPPORTED, "qc_qlinear_asym_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def qlinear_asym_t(X, pw: PackedWeight, row_sums, bias=None, epi="none", out="bf16", workspace=None,
+                   Y=None, act_bits: int = 8):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == pw.K
+    M, K = X.shape
+    if workspace is None:
+        workspace = qlinear_asym_workspace_t(M, K, pw.N, X.device)
+    if Y is None:
+        ydtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[out]
+        Y = torch.empty((M, pw.N), dtype=ydtype, device=X.device)
+    _check(qc_qlinear_asym(X.data_ptr(), _xdt(X), M, K, act_bits, pw.blob.data_ptr(),
+                           pw.scale.data_ptr(), row_sums.data_ptr(), pw.bits, pw.N,
+                           None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
+                           OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
+           "qc_qlinear_asym")
+    return Y
+
+
+def debug_workspace_act_asym_t(workspace, M: int, K: int, act_bits: int = 8):
+    torch = _torch()
+    qx = torch.empty((M, K), dtype=torch.uint8, device=workspace.device)
+    sx = torch.empty(M, dtype=torch.float32, device=workspace.device)
+    zx = torch.empty(M, dtype=torch.float32, device=workspace.device)
+    _check(qc_debug_workspace_act_asym(workspace.data_ptr(), M, K, act_bits, qx.data_ptr(),
+                                       sx.data_ptr(), zx.data_ptr(), _stream()),
+           "qc_debug_workspace_act_asym")
+    return qx, sx, zx

@@ -51,6 +51,8 @@ struct StageLayout {
 struct GemmArgs {
     const uint8_t *x_tiled;
     const float *x_scale;   // Mp entries (padded), 16 B aligned
+    const float *x_corr;    // asymmetric activations only: per token 2^(b-1) - zero point, Mp entries
+    const int32_t *w_rowsum;  // asymmetric activations only: per channel sum of the weight codes
     const uint8_t *w_codes;
     const float *w_scale;
     const float *bias;
@@ -102,7 +104,10 @@ __device__ inline void tile_of_block(int b, int nblocks, int m_tiles, int n_tile
 #define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 #define QC_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
-template <int BITS, int OUT, int EPI>
+// ASYM: the activation codes are the unsigned codes of the asymmetric quantizer minus 2^(b-1)
+// (Section 3.1 Eq. (3)-(4) as printed).  With c[m] = 2^(b-1) - z[m] the dequantized activation
+// is sx (code + c), so the epilogue adds c[m] * sum_k qw[n, k] to the accumulator.
+template <int BITS, int OUT, int EPI, bool ASYM>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     using L = StageLayout<BITS>;
     constexpr int FPW = L::kFragsPerWave;
@@ -120,14 +125,21 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     float *lds_sx = reinterpret_cast<float *>(lds + kStages * L::kBytes);  // 256 token scales
     float *lds_sw = lds_sx + kTileM;                                       // 128 channel scales
     float *lds_bs = lds_sw + kTileN;                                       // 128 biases
-    float my_sx = 0.0f, my_sw = 0.0f, my_bs = 0.0f;
+    float *lds_cx = lds_bs + kTileN;                                       // ASYM: 256 corrections
+    float *lds_rs = lds_cx + kTileM;                                       // ASYM: 128 code sums
+    float my_sx = 0.0f, my_sw = 0.0f, my_bs = 0.0f, my_cx = 0.0f, my_rs = 0.0f;
     if (OUT != QC_OUT_I32_ACC) {
         my_sx = a.x_scale[(int64_t)mt * kTileM + threadIdx.x];  // x_scale is padded to Mp
+        if (ASYM) my_cx = a.x_corr[(int64_t)mt * kTileM + threadIdx.x];
         const int64_t n = (int64_t)nt * kTileN + threadIdx.x;
         if (threadIdx.x < kTileN && n < a.N) {
             my_sw = a.w_scale[n];
             if (BITS == 4) my_sw *= 0.0625f;  // operands carry codes times 16
             if (a.bias) my_bs = a.bias[n];
+            if (ASYM) {
+                my_rs = (float)a.w_rowsum[n];  // |sum| <= 127 K < 2^24: exact
+                if (BITS == 4) my_rs *= 16.0f;
+            }
         }
     }
     // Weight fragments this wavefront copies HBM -> LDS, at stage 0.
@@ -292,6 +304,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     if (OUT != QC_OUT_I32_ACC) {
         lds_sx[threadIdx.x] = my_sx;
         if (threadIdx.x < kTileN) { lds_sw[threadIdx.x] = my_sw; lds_bs[threadIdx.x] = my_bs; }
+        if (ASYM) {
+            lds_cx[threadIdx.x] = my_cx;
+            if (threadIdx.x < kTileN) lds_rs[threadIdx.x] = my_rs;
+        }
         __syncthreads();
     }
 
@@ -304,12 +320,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     if (n0 >= a.N) return;
     const bool full = (a.N % 4) == 0 && n0 + 4 <= a.N;
 
-    float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f};
+    float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f}, rs[4] = {0.f, 0.f, 0.f, 0.f};
     if (OUT != QC_OUT_I32_ACC) {
         const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 4 * c);
         const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 4 * c);
         sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
         bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
+        if (ASYM) {
+            const float4 r4 = *reinterpret_cast<const float4 *>(lds_rs + 4 * c);
+            rs[0] = r4.x; rs[1] = r4.y; rs[2] = r4.z; rs[3] = r4.w;
+        }
     }
 
 #pragma unroll
@@ -318,10 +338,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         for (int g = 0; g < 4; ++g) {
             const int64_t m4 = m0 + 32 * i + 8 * g;
             if (m4 >= a.M) continue;
-            float sx[4] = {0.f, 0.f, 0.f, 0.f};
+            float sx[4] = {0.f, 0.f, 0.f, 0.f}, cx[4] = {0.f, 0.f, 0.f, 0.f};
             if (OUT != QC_OUT_I32_ACC) {
                 const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * 64 + 4 * h + 32 * i + 8 * g);
                 sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
+                if (ASYM) {
+                    const float4 c4 = *reinterpret_cast<const float4 *>(lds_cx + wave * 64 + 4 * h + 32 * i + 8 * g);
+                    cx[0] = c4.x; cx[1] = c4.y; cx[2] = c4.z; cx[3] = c4.w;
+                }
             }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -346,7 +370,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                     float v[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        float y = fmaf((float)raw[t] * sx[q], sw[t], bs[t]);
+                        float af = (float)raw[t];
+                        if (ASYM) af = fmaf(cx[q], rs[t], af);
+                        float y = fmaf(af * sx[q], sw[t], bs[t]);
                         if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
                         else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
                         v[t] = y;
@@ -377,10 +403,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     }
 }
 
-template <int BITS, int OUT, int EPI>
+template <int BITS, int OUT, int EPI, bool ASYM>
 hipError_t launch_variant(const GemmArgs &args, hipStream_t stream) {
     using L = StageLayout<BITS>;
-    constexpr int kLds = kStages * L::kBytes + (kTileM + 2 * kTileN) * (int)sizeof(float);
+    constexpr int kLds = kStages * L::kBytes +
+                         (kTileM + 2 * kTileN + (ASYM ? kTileM + kTileN : 0)) * (int)sizeof(float);
     // The attribute belongs to the function on one device: set it once per device (setting it
     // twice, as two threads racing here may, is harmless).
     static std::atomic<uint64_t> configured{0};
@@ -388,24 +415,25 @@ hipError_t launch_variant(const GemmArgs &args, hipStream_t stream) {
     if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
     const uint64_t bit = 1ull << (device & 63);
     if (!(configured.load(std::memory_order_acquire) & bit)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, OUT, EPI>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, OUT, EPI, ASYM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         configured.fetch_or(bit, std::memory_order_release);
     }
     const int blocks = args.m_tiles * args.n_tiles;
-    gemm_kernel<BITS, OUT, EPI><<<dim3((unsigned)blocks), dim3(kThreads), kLds, stream>>>(args);
+    gemm_kernel<BITS, OUT, EPI, ASYM><<<dim3((unsigned)blocks), dim3(kThreads), kLds, stream>>>(args);
     return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, bool ASYM>
 hipError_t launch_bits(const GemmArgs &args, qc_epilogue epi, qc_out ydt, hipStream_t stream) {
-    if (ydt == QC_OUT_I32_ACC) return launch_variant<BITS, QC_OUT_I32_ACC, QC_EPI_NONE>(args, stream);
+    // the raw accumulators are the same kernel with or without a zero point
+    if (ydt == QC_OUT_I32_ACC) return launch_variant<BITS, QC_OUT_I32_ACC, QC_EPI_NONE, false>(args, stream);
 #define QC_EPI_CASE(O)                                                                        \
     switch (epi) {                                                                            \
-        case QC_EPI_NONE: return launch_variant<BITS, O, QC_EPI_NONE>(args, stream);          \
-        case QC_EPI_GELU_TANH: return launch_variant<BITS, O, QC_EPI_GELU_TANH>(args, stream);\
-        default: return launch_variant<BITS, O, QC_EPI_GELU_ERF>(args, stream);               \
+        case QC_EPI_NONE: return launch_variant<BITS, O, QC_EPI_NONE, ASYM>(args, stream);         \
+        case QC_EPI_GELU_TANH: return launch_variant<BITS, O, QC_EPI_GELU_TANH, ASYM>(args, stream);\
+        default: return launch_variant<BITS, O, QC_EPI_GELU_ERF, ASYM>(args, stream);             \
     }
     if (ydt == QC_OUT_F32) { QC_EPI_CASE(QC_OUT_F32) }
     QC_EPI_CASE(QC_OUT_BF16)
@@ -416,10 +444,13 @@ hipError_t launch_bits(const GemmArgs &args, qc_epilogue epi, qc_out ydt, hipStr
 
 hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8_t *w_packed,
                        const float *w_scale, const float *bias, void *Y, int64_t M, int64_t N,
-                       int64_t K, int bits, qc_epilogue epi, qc_out ydt, hipStream_t stream) {
+                       int64_t K, int bits, qc_epilogue epi, qc_out ydt, const float *x_corr,
+                       const int32_t *w_rowsum, hipStream_t stream) {
     GemmArgs args;
     args.x_tiled = x_tiled;
     args.x_scale = x_scale;
+    args.x_corr = x_corr;
+    args.w_rowsum = w_rowsum;
     args.w_codes = w_packed + kPackedHeaderBytes;
     args.w_scale = w_scale;
     args.bias = bias;
@@ -429,7 +460,11 @@ hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8
     args.KF = (int)(round_up(K, kKAlign) / kFragK);
     args.m_tiles = (int)(round_up(M, kTileM) / kTileM);
     args.n_tiles = (int)(round_up(N, kTileN) / kTileN);
-    return bits == 8 ? launch_bits<8>(args, epi, ydt, stream) : launch_bits<4>(args, epi, ydt, stream);
+    if (x_corr && w_rowsum)
+        return bits == 8 ? launch_bits<8, true>(args, epi, ydt, stream)
+                         : launch_bits<4, true>(args, epi, ydt, stream);
+    return bits == 8 ? launch_bits<8, false>(args, epi, ydt, stream)
+                     : launch_bits<4, false>(args, epi, ydt, stream);
 }
 
 }  // namespace qc

@@ -72,9 +72,33 @@ hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, i
                             uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
                             int rot_block, hipStream_t stream);
 bool quant_rotation_supported(int64_t K, int rot_block);
+// K the vector quantization kernels take: a multiple of 16, at most 9216
+bool quant_vector_path(int64_t K);
+// Asymmetric codes (Section 3.1 Eq. (3)-(4) as printed).  shifted = false: canonical unsigned
+// codes and x_aux = zero point; shifted = true: codes minus 2^(b-1) as signed bytes and
+// x_aux = 2^(b-1) - zero point, what the GEMM consumes.
+hipError_t launch_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K, uint8_t *qx_rowmajor,
+                                 uint8_t *qx_tiled, int64_t KF, float *x_scale, float *x_aux,
+                                 int act_bits, bool shifted, hipStream_t stream);
+
+// workspace of qc_qlinear_asym: [ x_scale: Mp floats ][ x_corr: Mp floats ][ tiled codes ]
+struct ActWorkspaceAsym {
+    ActWorkspace sym;
+    size_t corr_offset, codes_offset, total_bytes;
+};
+
+__host__ inline ActWorkspaceAsym act_workspace_asym(int64_t M, int64_t K) {
+    ActWorkspaceAsym w;
+    w.sym = act_workspace(M, K);
+    w.corr_offset = w.sym.scale_bytes;
+    w.codes_offset = 2 * w.sym.scale_bytes;
+    w.total_bytes = w.sym.total_bytes + w.sym.scale_bytes;
+    return w;
+}
 
 hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8_t *w_packed,
                        const float *w_scale, const float *bias, void *Y, int64_t M, int64_t N,
-                       int64_t K, int bits, qc_epilogue epi, qc_out ydt, hipStream_t stream);
+                       int64_t K, int bits, qc_epilogue epi, qc_out ydt, const float *x_corr,
+                       const int32_t *w_rowsum, hipStream_t stream);
 
 }  // namespace qc

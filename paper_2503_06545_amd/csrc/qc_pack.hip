@@ -137,6 +137,61 @@ __global__ __launch_bounds__(kThreads) void unpack_weight_kernel(const uint8_t *
     }
 }
 
+// Sum of the codes of each output channel, read back from the packed blob (one wavefront per
+// channel).  The epilogue of the asymmetric-activation linear multiplies it by the token's
+// zero-point correction.
+__global__ __launch_bounds__(kThreads) void weight_row_sums_kernel(const uint8_t *__restrict__ blob,
+                                                                   int64_t N, int64_t K, int bits,
+                                                                   int64_t Kp,
+                                                                   int32_t *__restrict__ sums) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const uint8_t *codes = blob + kPackedHeaderBytes;
+    const int64_t KF = Kp / kFragK;
+    const int64_t p = weight_row_of_channel(n);
+    int32_t acc = 0;
+    for (int64_t k8 = (int64_t)lane * 8; k8 < K; k8 += 64 * 8) {
+        if (bits == 8) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(codes + frag_offset(p, k8, KF));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t w = e < 4 ? v.x : v.y;
+                if (k8 + e < K) acc += (int32_t)(int8_t)((w >> (8 * (e & 3))) & 0xff);
+            }
+        } else {
+            const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(p, k8, KF));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int nib = (int)((v >> (4 * w4_nibble_of(e))) & 0xf);
+                if (k8 + e < K) acc += nib >= 8 ? nib - 16 : nib;
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d);
+    if (lane == 0) sums[n] = acc;
+}
+
+// The same for the workspace of the asymmetric linear: unsigned codes back from the stored
+// signed bytes (code - 2^(b-1)), zero point back from the stored correction 2^(b-1) - z.
+__global__ __launch_bounds__(kThreads) void untile_act_asym_kernel(const uint8_t *__restrict__ tiled,
+                                                                   const float *__restrict__ scales,
+                                                                   const float *__restrict__ corr,
+                                                                   int64_t M, int64_t K, int64_t KF,
+                                                                   int shift, uint8_t *__restrict__ qx,
+                                                                   float *__restrict__ x_scale,
+                                                                   float *__restrict__ x_zero) {
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx < M) {
+        x_scale[idx] = scales[idx];
+        x_zero[idx] = (float)shift - corr[idx];
+    }
+    if (idx >= M * K) return;
+    const int64_t m = idx / K, k = idx % K;
+    qx[idx] = (uint8_t)((int)(int8_t)tiled[frag_offset(m, k, KF)] + shift);
+}
+
 __global__ __launch_bounds__(kThreads) void untile_act_kernel(const uint8_t *__restrict__ tiled,
                                                               const float *__restrict__ scales,
                                                               int64_t M, int64_t K, int64_t KF,
@@ -211,5 +266,33 @@ extern "C" qc_status qc_debug_workspace_act(const void *workspace, int64_t M, in
     const int64_t blocks = (M * K + kThreads - 1) / kThreads;
     untile_act_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
         base + ws.scale_bytes, (const float *)base, M, K, ws.KF, qx, x_scale);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_weight_row_sums(const void *packed, int64_t N, int64_t K, int bits,
+                                        int32_t *row_sums, void *stream) {
+    if (!packed || !row_sums || N < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(row_sums, 16)) return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const int64_t Kp = round_up(K, kKAlign);
+    const int64_t blocks = (N + kThreads / 64 - 1) / (kThreads / 64);
+    weight_row_sums_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        (const uint8_t *)packed, N, K, bits, Kp, row_sums);
+    return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t M, int64_t K,
+                                                 int act_bits, uint8_t *qx, float *x_scale,
+                                                 float *x_zero, void *stream) {
+    if (!workspace || !qx || !x_scale || !x_zero || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (act_bits != 8 && act_bits != 6 && act_bits != 4) return QC_ERR_UNSUPPORTED;
+    if (K > QC_MAX_K) return QC_ERR_UNSUPPORTED;
+    if (!aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    const ActWorkspaceAsym ws = act_workspace_asym(M, K);
+    const uint8_t *base = (const uint8_t *)workspace;
+    const int64_t blocks = (M * K + kThreads - 1) / kThreads;
+    untile_act_asym_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        base + ws.codes_offset, (const float *)base, (const float *)(base + ws.corr_offset), M, K,
+        ws.sym.KF, 1 << (act_bits - 1), qx, x_scale, x_zero);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }

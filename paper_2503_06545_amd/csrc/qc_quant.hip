@@ -270,6 +270,98 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
     }
 }
 
+// ---- the quantizer as printed, asymmetric (Section 3.1 Eq. (3)-(4)) ----------------------------
+//   s = max(hi - lo, 2^-64) / levels,  z = -rne(lo / s),  code = clamp(rne(x / s) + z, 0, levels)
+// with levels = 2^b - 1.  Same layout and the same division-free quotient as above (it is
+// exact for these larger quotients as well, checked on the host).  `shifted` selects what is
+// stored: the canonical unsigned code and z, or, for the GEMM, code - 2^(b-1) as a signed byte
+// and the correction 2^(b-1) - z.
+template <typename XT>
+__global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
+    const XT *__restrict__ X, int64_t M, int64_t K, uint8_t *__restrict__ qx,
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale,
+    float *__restrict__ x_aux, float levels, float shift, bool shifted) {
+    __shared__ float slice_lo[kMaxSlices][kRowsPerBlock], slice_hi[kMaxSlices][kRowsPerBlock];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6, slices = blockDim.x >> 6;
+    const int sub = lane % kLanesPerRow, row_in_block = lane / kLanesPerRow;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + row_in_block;
+    const int units = (int)(K / kUnit);
+    const bool live = row < M;
+    const XT *xrow = X + (live ? row : 0) * K;
+
+    Unit<XT> u[kUnitsPerThread];
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
+        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        else u[i].zero();
+    }
+
+    // units past the end of the row hold zeros, which must not enter the minimum or maximum
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
+        if (ui < units) {
+#pragma unroll
+            for (int e = 0; e < kUnit; ++e) {
+                lo = fminf(lo, u[i].get(e));
+                hi = fmaxf(hi, u[i].get(e));
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < kLanesPerRow; d <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, d));
+        hi = fmaxf(hi, __shfl_xor(hi, d));
+    }
+    if (slices > 1) {  // uniform over the block
+        if (sub == 0) { slice_lo[slice][row_in_block] = lo; slice_hi[slice][row_in_block] = hi; }
+        __syncthreads();
+        for (int sl = 0; sl < slices; ++sl) {
+            lo = fminf(lo, slice_lo[sl][row_in_block]);
+            hi = fmaxf(hi, slice_hi[sl][row_in_block]);
+        }
+    }
+    if (!live) return;
+
+    const float s = fmaxf(hi - lo, kAbsmaxFloor) / levels;
+    const float r = 1.0f / s;  // correctly rounded
+    const float z = -rintf(quotient(lo, s, r));
+    if (sub == 0 && slice == 0) {
+        x_scale[row] = s;
+        x_aux[row] = shifted ? shift - z : z;
+    }
+    // clamp(rne(q) + z, 0, levels) - shift = clamp(rne(q) + (z - shift), -shift, levels - shift)
+    const float off = shifted ? z - shift : z;
+    const float cmin = shifted ? -shift : 0.0f, cmax = shifted ? levels - shift : levels;
+    const float magic = 12582912.0f;  // 1.5 * 2^23: the sum's low byte is the integer's low byte
+
+    uint8_t *out_rows = qx ? qx + row * K : nullptr;
+    uint8_t *out_tiled = qx_tiled ? qx_tiled + (row / kFragRows) * KF * kFragBytes + (row % kFragRows) * 16
+                                  : nullptr;
+#pragma unroll
+    for (int i = 0; i < kUnitsPerThread; ++i) {
+        const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
+        if (ui >= units) continue;
+        uint32_t w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = rintf(quotient(u[i].get(4 * d + e), s, r)) + off;
+                y[e] = __float_as_uint(__builtin_amdgcn_fmed3f(v, cmin, cmax) + magic);
+            }
+            w[d] = __builtin_amdgcn_perm(y[1], y[0], 0x0c0c0400u) | __builtin_amdgcn_perm(y[3], y[2], 0x04000c0cu);
+        }
+        const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
+        if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
+        if (out_tiled)
+            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 1) * kFragBytes + (ui & 1) * 512) = out;
+    }
+}
+
 // Any K, any alignment: one wavefront per row, two passes over the row (the second one is
 // served by the caches).  Slow path for shapes the vector kernel does not take.
 template <typename XT>
@@ -323,6 +415,26 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
 }
 
 }  // namespace
+
+bool quant_vector_path(int64_t K) {
+    return K % kUnit == 0 && K / kUnit <= (int64_t)kUnitsPerSlice * kMaxSlices;
+}
+
+hipError_t launch_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K, uint8_t *qx_rowmajor,
+                                 uint8_t *qx_tiled, int64_t KF, float *x_scale, float *x_aux,
+                                 int act_bits, bool shifted, hipStream_t stream) {
+    if (!quant_vector_path(K)) return hipErrorInvalidValue;  // the entry points reject these first
+    const float levels = (float)((1 << act_bits) - 1), shift = (float)(1 << (act_bits - 1));
+    const int64_t slices = (K / kUnit + kUnitsPerSlice - 1) / kUnitsPerSlice;
+    const dim3 grid((unsigned)((M + kRowsPerBlock - 1) / kRowsPerBlock)), block((unsigned)(64 * slices));
+    if (xdt == QC_BF16)
+        quant_rows_asym_kernel<uint16_t><<<grid, block, 0, stream>>>(
+            (const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, x_aux, levels, shift, shifted);
+    else
+        quant_rows_asym_kernel<float><<<grid, block, 0, stream>>>(
+            (const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, x_aux, levels, shift, shifted);
+    return hipGetLastError();
+}
 
 bool quant_rotation_supported(int64_t K, int rot_block) {
     if (rot_block != 16 && rot_block != 32 && rot_block != 64 && rot_block != 128) return false;

@@ -25,9 +25,49 @@ static float code_of(float q) { return fminf(fmaxf(rintf(q), -qmax), qmax); }
 static uint64_t state = 88172645463325252ULL;
 static uint64_t next(void) { state ^= state << 13; state ^= state >> 7; state ^= state << 17; return state; }
 
+/* The asymmetric quantizer (unsigned codes, zero point per row) uses the same quotient for
+ * x / s and for min / s, with quotients far above the code range when a row lies far from
+ * zero.  Rows [lo, hi] of either sign with |lo| / (hi - lo) up to 2^20; x anywhere in the row,
+ * its ends included, half of them truncated to bf16.  Counts rows * samples, rounded quotients
+ * that differ, and final codes that differ. */
+static int asym_main(long rows, long per_row, float levels) {
+    long pairs = 0, bad_round = 0, bad_code = 0;
+    for (long it = 0; it < rows; ++it) {
+        uint32_t ab = (uint32_t)(next() & 0x7fffffff);
+        float range, lo;
+        memcpy(&range, &ab, 4);
+        if (!(range > 0x1p-40f && range < 0x1p40f)) continue;
+        float ratio = ldexpf((float)(next() & 0xffff) / 65536.0f, (int)(next() % 22) - 1);
+        lo = range * ratio * ((next() & 1) ? 1.0f : -1.0f) - ((next() & 2) ? range * 0.5f : 0.0f);
+        if (it & 4) { uint32_t u; memcpy(&u, &lo, 4); u &= 0xffff0000u; memcpy(&lo, &u, 4); }
+        float hi = lo + range;
+        float span = hi - lo;
+        if (!(span > 0.0f)) continue;
+        float s = span / levels, r = 1.0f / s;
+        float z_true = -rintf(lo / s), z_fast = -rintf(fast_quotient(lo, s, r));
+        if (z_true != z_fast) ++bad_round;
+        for (long j = 0; j < per_row; ++j) {
+            float x;
+            if (j == 0) x = lo;
+            else if (j == 1) x = hi;
+            else x = lo + span * ((float)(next() & 0xffffff) / 16777215.0f);
+            if (j & 1) { uint32_t u; memcpy(&u, &x, 4); u &= 0xffff0000u; memcpy(&x, &u, 4); }
+            if (!(x >= lo && x <= hi)) continue;
+            float a = rintf(x / s), b = rintf(fast_quotient(x, s, r));
+            ++pairs;
+            if (a != b) ++bad_round;
+            float ca = fminf(fmaxf(a + z_true, 0.0f), levels), cb = fminf(fmaxf(b + z_fast, 0.0f), levels);
+            if (ca != cb) ++bad_code;
+        }
+    }
+    printf("%ld %ld %ld\n", pairs, bad_round, bad_code);
+    return 0;
+}
+
 int main(int argc, char **argv) {
     long scales = argc > 1 ? atol(argv[1]) : 400, randoms = argc > 2 ? atol(argv[2]) : 20000000;
     if (argc > 3) qmax = (float)atof(argv[3]);
+    if (argc > 4 && strcmp(argv[4], "asym") == 0) return asym_main(scales, randoms, qmax);
     long pairs = 0, bad_q = 0, bad_code = 0;
     for (long si = 0; si < scales; ++si) {
         uint32_t ab = (uint32_t)(next() & 0x7fffffff);

@@ -22,3 +22,10 @@ def test_reciprocal_plus_two_fma_corrections_equals_ieee_division():
             pairs, bad_quotients, bad_codes = (int(v) for v in out.stdout.split())
             assert pairs > 5_000_000
             assert bad_quotients == 0 and bad_codes == 0, (qmax, bad_quotients, bad_codes)
+        # the asymmetric quantizer: rows far from zero, quotients far above the code range
+        for levels in ("255", "63", "15"):
+            out = subprocess.run([exe, "1000000", "24", levels, "asym"], check=True,
+                                 capture_output=True, text=True)
+            pairs, bad_rounded, bad_codes = (int(v) for v in out.stdout.split())
+            assert pairs > 3_000_000
+            assert bad_rounded == 0 and bad_codes == 0, (levels, bad_rounded, bad_codes)

@@ -496,3 +496,113 @@ def test_qlinear_rot_leaves_the_product_and_cuts_outlier_error():
     y = host_f64(qc.qlinear_t(dev(xi), pw, None, "none", "f32", rot_block=128))
     want = xi.astype(np.float64) @ wi.astype(np.float64).T
     assert np.max(np.abs(y - want)) <= 1e-3 * 889
+
+
+# ------------------------------------------------------------------ asymmetric activations
+
+def post_gelu_x(rng, M, K, dtype):
+    g = rng.standard_normal((M, K))
+    x = (0.5 * g * (1 + np.tanh(0.7978845608 * (g + 0.044715 * g ** 3)))).astype(np.float32)
+    return synth.to_bf16_bits(x) if dtype == "bf16" else x
+
+
+@pytest.mark.parametrize("act_bits", [8, 6, 4])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K", [(256, 1152), (77, 4608), (9, 16), (33, 9216), (5, 2304)])
+def test_quant_act_asym_bit_exact(act_bits, dtype, M, K):
+    rng = np.random.default_rng(M * 31 + K + act_bits)
+    x = post_gelu_x(rng, M, K, dtype) if M % 2 else random_x(rng, M, K, dtype)
+    if dtype == "f32" and M > 8:
+        x[3] += np.float32(1000.0)     # a row far from zero: large zero point
+        x[4] = np.float32(-2.5)        # a constant row: range floor
+        x[5] = 0
+    q_ref, s_ref, z_ref = oracle.quant_act_asym(x, act_bits)
+    qx, sx, zx = qc.quant_act_asym_t(dev(x), act_bits)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), s_ref)
+    assert bits_equal(zx.cpu().numpy(), z_ref)
+    assert np.array_equal(qx.cpu().numpy(), q_ref)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K", [(1152, 1152), (200, 136), (3, 16), (129, 4608)])
+def test_weight_row_sums_exact(bits, N, K):
+    rng = np.random.default_rng(N + K + bits)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    W[0] = np.abs(W[0])                     # a channel whose codes do not cancel
+    q_ref, _ = oracle.quant_weight(W, bits)
+    pw = qc.pack_weight_t(dev(W), bits)
+    sums = qc.weight_row_sums_t(pw).cpu().numpy()
+    assert np.array_equal(sums, q_ref.astype(np.int64).sum(axis=1))
+
+
+def run_asym_case(x, W, b, bits, epi, out, act_bits=8):
+    M, K = x.shape
+    N = W.shape[0]
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    ref = oracle.qlinear_asym(x, qw_ref, sw_ref, b, EPI_ORACLE[epi], act_bits)
+    xd, pw = dev(x), qc.pack_weight_t(dev(W), bits)
+    rs = qc.weight_row_sums_t(pw)
+    bd = None if b is None else dev(b)
+    ws = qc.qlinear_asym_workspace_t(M, K, N)
+    y = qc.qlinear_asym_t(xd, pw, rs, bd, epi, out, workspace=ws, act_bits=act_bits)
+    qx, sx, zx = qc.debug_workspace_act_asym_t(ws, M, K, act_bits)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), ref["sx"]), "activation scales differ"
+    assert np.array_equal(zx.cpu().numpy(), ref["zx"]), "zero points differ"
+    assert np.array_equal(qx.cpu().numpy(), ref["qx"]), "activation codes differ"
+    # the MFMA loop's own sum, on the stored signed bytes
+    acc = qc.qlinear_asym_t(xd, pw, rs, None, "none", "i32", workspace=ws, act_bits=act_bits)
+    shifted = (ref["qx"].astype(np.int16) - (1 << (act_bits - 1))).astype(np.int8)
+    assert np.array_equal(acc.cpu().numpy(), oracle.gemm_i32(shifted, qw_ref))
+    y_ref = ref["y"]
+    if out == "bf16":
+        y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(y_ref))
+    else:
+        y_ref = oracle.round_f32(y_ref).astype(np.float64)
+    assert_outputs_close(host_f64(y), y_ref, RTOL[out])
+    return host_f64(y)
+
+
+@pytest.mark.parametrize("bits,act_bits", [(8, 8), (4, 8), (4, 6), (8, 4)])
+@pytest.mark.parametrize("epi,out", [("none", "f32"), ("gelu_tanh", "bf16")])
+def test_qlinear_asym_matches_oracle(bits, act_bits, epi, out):
+    rng = np.random.default_rng(bits * 100 + act_bits)
+    M, K, N = 520, 1152, 300
+    x = post_gelu_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_asym_case(x, W, b, bits, epi, out, act_bits=act_bits)
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 16, 1), (257, 64, 129), (33, 208, 77), (700, 4608, 130)])
+def test_qlinear_asym_ragged_shapes(M, K, N):
+    rng = np.random.default_rng(M + 3 * K + 5 * N)
+    x = random_x(rng, M, K, "f32") + np.float32(0.75)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_asym_case(x, W, b, 8, "none", "f32")
+    run_asym_case(x, W, None, 4, "gelu_erf", "bf16")
+
+
+def test_qlinear_asym_gains_on_one_sided_input_and_is_exact_on_integers():
+    rng = np.random.default_rng(7)
+    M, K, N = 512, 4608, 256
+    x = post_gelu_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    qw, sw = oracle.quant_weight(W, 8)
+    exact = oracle.bf16_bits_to_f64(x) @ (sw.astype(np.float64)[:, None] * qw.astype(np.float64)).T
+    pw = qc.pack_weight_t(dev(W), 8)
+    rs = qc.weight_row_sums_t(pw)
+    for act_bits in (8, 4):
+        e_sym = np.abs(host_f64(qc.qlinear_t(dev(x), pw, None, "none", "f32", act_bits=act_bits)) - exact).mean()
+        e_asym = np.abs(host_f64(qc.qlinear_asym_t(dev(x), pw, rs, None, "none", "f32", act_bits=act_bits)) - exact).mean()
+        assert e_asym < 0.7 * e_sym, (act_bits, e_asym, e_sym)
+    Xi = rng.integers(0, 256, size=(64, 1152)).astype(np.float32)
+    Xi[:, 0], Xi[:, 1] = 0, 255
+    Wi = rng.integers(-127, 128, size=(128, 1152)).astype(np.float32)
+    Wi[:, 0] = 127
+    pwi = qc.pack_weight_t(dev(Wi), 8)
+    y = host_f64(qc.qlinear_asym_t(dev(Xi - 100), pwi, qc.weight_row_sums_t(pwi), None, "none", "f32"))
+    want = (Xi.astype(np.float64) - 100) @ Wi.astype(np.float64).T
+    assert np.max(np.abs(y - want)) <= 2e-7 * np.max(np.abs(want)) * 4
