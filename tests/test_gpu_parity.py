@@ -205,6 +205,21 @@ def test_qlinear_ragged_shapes(bits, M, K, N):
     run_linear_case(synth.to_bf16_bits(x), W, None, bits, "gelu_tanh", "bf16", check_acc=False)
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,N", [(4096, 4096), (4096 - 37, 4096 - 3)])
+def test_qlinear_many_tiles_full_comparison(bits, M, N):
+    """Several rounds of tiles on every CU (512 tiles of 256 x 128), short reduction; the whole
+    output is compared with the oracle, ragged edges included."""
+    rng = np.random.default_rng(M + N + bits)
+    K = 320
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    run_linear_case(x, W, b, bits, "gelu_tanh", "bf16")
+    if bits == 4:
+        run_asym_case(x, W, b, bits, "none", "f32", act_bits=6)
+
+
 def test_qlinear_closed_form_integers_and_extremes():
     """Integer operands with unit scales reproduce X W^T + b exactly; all-127 operands reach the
     largest accumulator magnitude at K = 4608."""
