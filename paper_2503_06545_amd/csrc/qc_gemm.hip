@@ -317,90 +317,100 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     const int c = lane & 31, h = lane >> 5;
     const int64_t n0 = (int64_t)nt * kTileN + 4 * c;
     const int64_t m0 = (int64_t)mt * kTileM + wave * 64 + 4 * h;
-    if (n0 >= a.N) return;
-    const bool full = (a.N % 4) == 0 && n0 + 4 <= a.N;
+    // A tile that lies wholly inside Y (the common case) takes a straight-line path with
+    // vector stores and no per-row tests; edge tiles test every row and channel.
+    const bool interior = (int64_t)(mt + 1) * kTileM <= a.M && (int64_t)(nt + 1) * kTileN <= a.N &&
+                          (a.N % 4) == 0;  // uniform over the block
 
-    float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f}, rs[4] = {0.f, 0.f, 0.f, 0.f};
-    if (OUT != QC_OUT_I32_ACC) {
-        const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 4 * c);
-        const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 4 * c);
-        sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
-        bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
-        if (ASYM) {
-            const float4 r4 = *reinterpret_cast<const float4 *>(lds_rs + 4 * c);
-            rs[0] = r4.x; rs[1] = r4.y; rs[2] = r4.z; rs[3] = r4.w;
-        }
-    }
+    auto write_tile = [&](auto checked_tag) {
+        constexpr bool CHECKED = decltype(checked_tag)::value;
+        if (CHECKED && n0 >= a.N) return;
+        const bool full = !CHECKED || ((a.N % 4) == 0 && n0 + 4 <= a.N);
 
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int64_t m4 = m0 + 32 * i + 8 * g;
-            if (m4 >= a.M) continue;
-            float sx[4] = {0.f, 0.f, 0.f, 0.f}, cx[4] = {0.f, 0.f, 0.f, 0.f};
-            if (OUT != QC_OUT_I32_ACC) {
-                const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * 64 + 4 * h + 32 * i + 8 * g);
-                sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
-                if (ASYM) {
-                    const float4 c4 = *reinterpret_cast<const float4 *>(lds_cx + wave * 64 + 4 * h + 32 * i + 8 * g);
-                    cx[0] = c4.x; cx[1] = c4.y; cx[2] = c4.z; cx[3] = c4.w;
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t m = m4 + q;
-                if (m >= a.M) continue;
-                int raw[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) raw[t] = acc[i][t][4 * g + q];
-                if (OUT == QC_OUT_I32_ACC) {
-                    int32_t *y = reinterpret_cast<int32_t *>(a.Y) + m * a.N + n0;
-                    if (BITS == 4) {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
-                    }
-                    if (full) {
-                        __builtin_nontemporal_store(v4i{raw[0], raw[1], raw[2], raw[3]}, reinterpret_cast<v4i *>(y));
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
-                    }
-                } else {
-                    float v[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        float af = (float)raw[t];
-                        if (ASYM) af = fmaf(cx[q], rs[t], af);
-                        float y = fmaf(af * sx[q], sw[t], bs[t]);
-                        if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
-                        else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
-                        v[t] = y;
-                    }
-                    if (OUT == QC_OUT_F32) {
-                        float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
-                        if (full) {
-                            __builtin_nontemporal_store(f4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f4 *>(y));
-                        } else {
-#pragma unroll
-                            for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
-                        }
-                    } else {
-                        uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
-                        const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
-                        if (full) {
-                            __builtin_nontemporal_store(u2{lo, hi}, reinterpret_cast<u2 *>(y));
-                        } else {
-                            if (n0 + 0 < a.N) y[0] = (uint16_t)(lo & 0xffffu);
-                            if (n0 + 1 < a.N) y[1] = (uint16_t)(lo >> 16);
-                            if (n0 + 2 < a.N) y[2] = (uint16_t)(hi & 0xffffu);
-                            if (n0 + 3 < a.N) y[3] = (uint16_t)(hi >> 16);
-                        }
-                    }
-                }
+        float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f}, rs[4] = {0.f, 0.f, 0.f, 0.f};
+        if (OUT != QC_OUT_I32_ACC) {
+            const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 4 * c);
+            const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 4 * c);
+            sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
+            bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
+            if (ASYM) {
+                const float4 r4 = *reinterpret_cast<const float4 *>(lds_rs + 4 * c);
+                rs[0] = r4.x; rs[1] = r4.y; rs[2] = r4.z; rs[3] = r4.w;
             }
         }
-    }
+
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t m4 = m0 + 32 * i + 8 * g;
+                if (CHECKED && m4 >= a.M) continue;
+                float sx[4] = {0.f, 0.f, 0.f, 0.f}, cx[4] = {0.f, 0.f, 0.f, 0.f};
+                if (OUT != QC_OUT_I32_ACC) {
+                    const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * 64 + 4 * h + 32 * i + 8 * g);
+                    sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
+                    if (ASYM) {
+                        const float4 c4 = *reinterpret_cast<const float4 *>(lds_cx + wave * 64 + 4 * h + 32 * i + 8 * g);
+                        cx[0] = c4.x; cx[1] = c4.y; cx[2] = c4.z; cx[3] = c4.w;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t m = m4 + q;
+                    if (CHECKED && m >= a.M) continue;
+                    int raw[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) raw[t] = acc[i][t][4 * g + q];
+                    if (OUT == QC_OUT_I32_ACC) {
+                        int32_t *y = reinterpret_cast<int32_t *>(a.Y) + m * a.N + n0;
+                        if (BITS == 4) {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
+                        }
+                        if (full) {
+                            __builtin_nontemporal_store(v4i{raw[0], raw[1], raw[2], raw[3]}, reinterpret_cast<v4i *>(y));
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
+                        }
+                    } else {
+                        float v[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            float af = (float)raw[t];
+                            if (ASYM) af = fmaf(cx[q], rs[t], af);
+                            float y = fmaf(af * sx[q], sw[t], bs[t]);
+                            if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
+                            else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
+                            v[t] = y;
+                        }
+                        if (OUT == QC_OUT_F32) {
+                            float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
+                            if (full) {
+                                __builtin_nontemporal_store(f4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f4 *>(y));
+                            } else {
+#pragma unroll
+                                for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
+                            }
+                        } else {
+                            uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
+                            const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
+                            if (full) {
+                                __builtin_nontemporal_store(u2{lo, hi}, reinterpret_cast<u2 *>(y));
+                            } else {
+                                if (n0 + 0 < a.N) y[0] = (uint16_t)(lo & 0xffffu);
+                                if (n0 + 1 < a.N) y[1] = (uint16_t)(lo >> 16);
+                                if (n0 + 2 < a.N) y[2] = (uint16_t)(hi & 0xffffu);
+                                if (n0 + 3 < a.N) y[3] = (uint16_t)(hi >> 16);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    };
+    if (interior) write_tile(std::false_type{});
+    else write_tile(std::true_type{});
 }
 
 template <int BITS, int OUT, int EPI, bool ASYM>
