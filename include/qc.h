@@ -52,6 +52,8 @@ typedef enum { QC_OUT_F32 = 0, QC_OUT_BF16 = 1, QC_OUT_I32_ACC = 2 } qc_out;
 
 /* Largest reduction length: 127 * 127 * K must stay below 2^31. */
 #define QC_MAX_K 131072
+/* Largest number of output channels (the GEMM addresses a row of Y with 32-bit lane offsets). */
+#define QC_MAX_N 67108864
 /* Most earlier tensors one qc_cumulative_variation call compares against. */
 #define QC_MAX_PREV 8
 
@@ -62,7 +64,7 @@ int qc_version(void);
 /* ---- sizes (host, pure functions) ------------------------------------------------ */
 
 /* Bytes of the opaque packed-weight blob for W [N, K] at `bits` (8 or 4).
- * 0 if the combination is unsupported (bits not 4/8, N or K < 1, K > QC_MAX_K,
+ * 0 if the combination is unsupported (bits not 4/8, N or K < 1, K > QC_MAX_K, N > QC_MAX_N,
  * bits == 4 with odd K). */
 size_t qc_packed_weight_bytes(int64_t N, int64_t K, int bits);
 

@@ -322,6 +322,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     const bool interior = (int64_t)(mt + 1) * kTileM <= a.M && (int64_t)(nt + 1) * kTileN <= a.N &&
                           (a.N % 4) == 0;  // uniform over the block
 
+    // Row addresses: a block-uniform base (scalar registers) plus one 32-bit lane offset that is
+    // the same for every row, so a row costs no vector address arithmetic.
+    constexpr int kOutBytes = OUT == QC_OUT_BF16 ? 2 : 4;
+    char *const y_wave = reinterpret_cast<char *>(a.Y) +
+                         (((int64_t)mt * kTileM + wave * 64) * a.N + (int64_t)nt * kTileN) * kOutBytes;
+    const uint32_t lane_off = (uint32_t)((4 * h * a.N + 4 * c) * kOutBytes);  // N <= 2^26
+
     auto write_tile = [&](auto checked_tag) {
         constexpr bool CHECKED = decltype(checked_tag)::value;
         if (CHECKED && n0 >= a.N) return;
@@ -361,8 +368,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                     int raw[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) raw[t] = acc[i][t][4 * g + q];
+                    char *const y_row = y_wave + (int64_t)(32 * i + 8 * g + q) * a.N * kOutBytes + lane_off;
                     if (OUT == QC_OUT_I32_ACC) {
-                        int32_t *y = reinterpret_cast<int32_t *>(a.Y) + m * a.N + n0;
+                        int32_t *y = reinterpret_cast<int32_t *>(y_row);
                         if (BITS == 4) {
 #pragma unroll
                             for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
@@ -385,7 +393,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                             v[t] = y;
                         }
                         if (OUT == QC_OUT_F32) {
-                            float *y = reinterpret_cast<float *>(a.Y) + m * a.N + n0;
+                            float *y = reinterpret_cast<float *>(y_row);
                             if (full) {
                                 __builtin_nontemporal_store(f4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f4 *>(y));
                             } else {
@@ -393,7 +401,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                                 for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
                             }
                         } else {
-                            uint16_t *y = reinterpret_cast<uint16_t *>(a.Y) + m * a.N + n0;
+                            uint16_t *y = reinterpret_cast<uint16_t *>(y_row);
                             const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
                             if (full) {
                                 __builtin_nontemporal_store(u2{lo, hi}, reinterpret_cast<u2 *>(y));

@@ -212,7 +212,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 using namespace qc;
 
 extern "C" size_t qc_packed_weight_bytes(int64_t N, int64_t K, int bits) {
-    if ((bits != 4 && bits != 8) || N < 1 || K < 1 || K > QC_MAX_K) return 0;
+    if ((bits != 4 && bits != 8) || N < 1 || K < 1 || K > QC_MAX_K || N > QC_MAX_N) return 0;
     if (bits == 4 && (K % 2)) return 0;
     const int64_t Np = round_up(N, kTileN), Kp = round_up(K, kKAlign);
     return (size_t)kPackedHeaderBytes + (size_t)(Np * Kp * bits / 8);

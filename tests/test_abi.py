@@ -41,6 +41,7 @@ def test_size_queries():
     assert qc.qc_packed_weight_bytes(10, 16, 5) == 0
     assert qc.qc_packed_weight_bytes(0, 16, 8) == 0
     assert qc.qc_packed_weight_bytes(10, qc.QC_MAX_K + 1, 8) == 0
+    assert qc.qc_packed_weight_bytes((1 << 26) + 1, 16, 8) == 0
     assert qc.qc_qlinear_workspace_bytes(16384, 1152, 3456) == 16384 * 4 + 16384 * 1152
     assert qc.qc_qlinear_workspace_bytes(300, 100, 7) == 512 * 4 + 512 * 192
     assert qc.qc_qlinear_workspace_bytes(0, 100, 7) == 0
