@@ -7,7 +7,8 @@ W int8 [3456, 1152], bf16 out): qc_qlinear (per-token activation quantization + 
 GEMM + dequant/bias epilogue) followed by qc_latent_delta on two [16, 4, 16, 64, 64] float
 latents.  `--workload` selects the other STDiT layers (fc1+GELU, fc2 with int8 or int4
 weights) or the 28-block sweep (112 qc_qlinear calls, per-layer bit-width from the seeded
-importance mask).  Weights are packed once before the timed region (an offline step of the
+importance mask); `--variant` selects how the activations are quantized (lower bit-widths,
+rotation fused in, or the asymmetric form), the GEMM kernel being the same.  Weights are packed once before the timed region (an offline step of the
 method); the packing time is reported beside the result.  Inputs are resident in HBM when
 timing starts.
 
@@ -36,6 +37,11 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
 MEASURED_TRAFFIC_BYTES = {"qkv256": {"gemm": 166.3e6, "quant": 56.9e6, "delta": 33.6e6}}
 
 WORKLOADS = ("qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4", "sweep28")
+# How the activations are quantized: the spec form (symmetric int8 per token), the lower
+# activation bit-widths of Eq. (8), the rotation fused into the quantization, or the printed
+# asymmetric form of Eq. (3)-(4).  The GEMM is the same kernel in all of them.
+VARIANTS = {"a8": dict(act_bits=8), "a6": dict(act_bits=6), "a4": dict(act_bits=4),
+            "rot128": dict(act_bits=8, rot=128), "asym": dict(act_bits=8, asym=True)}
 
 
 def batch_times_us(fn, batch, rounds):
@@ -55,24 +61,32 @@ def batch_times_us(fn, batch, rounds):
     return {"avg_us": sum(t) / len(t), "min_us": min(t)}
 
 
-def cpu_baseline(case, target_seconds=15.0):
+def cpu_baseline(case, act_bits=8, rot=0, asym=False, target_seconds=15.0):
     """The oracle as it stands on a bounded sample of token rows (all N, all K)."""
     import oracle
     W, b = case.weight(), case.bias()
-    qw, sw = oracle.quant_weight(W, case.bits)
+    qw, sw = oracle.quant_weight_rot(W, case.bits, rot) if rot else oracle.quant_weight(W, case.bits)
     epi = {"none": oracle.EPI_NONE, "gelu_tanh": oracle.EPI_GELU_TANH,
            "gelu_erf": oracle.EPI_GELU_ERF}[case.epi]
+
+    def linear(x):
+        if asym:
+            return oracle.qlinear_asym(x, qw, sw, b, epi, act_bits)
+        if rot:
+            return oracle.qlinear_rot(x, qw, sw, rot, b, epi, act_bits)
+        return oracle.qlinear(x, qw, sw, b, epi, act_bits)
+
     threads = oracle.num_threads()
     probe_rows = 64
     x = case.x_rows(0, probe_rows)
     t0 = time.perf_counter()
-    oracle.qlinear(x, qw, sw, b, epi)
+    linear(x)
     per_row = (time.perf_counter() - t0) / probe_rows
     rows = int(min(case.M, max(probe_rows, target_seconds / per_row)))
     rows -= rows % 64
     x = case.x_rows(0, rows)
     t0 = time.perf_counter()
-    oracle.qlinear(x, qw, sw, b, epi)
+    linear(x)
     dt = time.perf_counter() - t0
     tops = 2.0 * rows * case.N * case.K / dt / 1e12
     return {"value": tops, "unit": "TOPS", "cores": threads, "kind": "oracle",
@@ -85,13 +99,14 @@ def cpu_baseline(case, target_seconds=15.0):
 class Layer:
     """Device buffers of one quantized linear."""
 
-    def __init__(self, case, x, ws, Y, layer_index=0):
+    def __init__(self, case, x, ws, Y, layer_index=0, rot=0, asym=False):
         import torch
         from paper_2503_06545_amd import binding as qc
         self.case, self.x, self.ws, self.Y = case, x, ws, Y
         self.W = torch.from_numpy(case.weight(layer_index)).cuda()
         self.bias = torch.from_numpy(case.bias(layer_index)).cuda()
-        self.pw = qc.pack_weight_t(self.W, case.bits)
+        self.pw = qc.pack_weight_t(self.W, case.bits, rot)
+        self.row_sums = qc.weight_row_sums_t(self.pw) if asym else None
         self.epi = qc.EPI[case.epi]
         self.ops = 2.0 * case.M * case.N * case.K
 
@@ -104,6 +119,10 @@ def main():
     # default warm-up is ~0.1 s of steps
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", choices=WORKLOADS, default="qkv256")
+    ap.add_argument("--variant", choices=tuple(VARIANTS), default="a8",
+                    help="activation quantizer: a8 (default), a6 / a4 (lower bit-widths), rot128 "
+                         "(Walsh-Hadamard rotation of 128-column blocks fused in), asym (zero "
+                         "point per token)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 256 MiB device copies, as the reference kernel "
@@ -159,13 +178,15 @@ def main():
     M = cases[0].M
     maxK = max(c.K for c in cases)
     maxN = max(c.N for c in cases)
-    ws = qc.qlinear_workspace_t(M, maxK, maxN)
+    var = VARIANTS[args.variant]
+    act_bits, rot, asym = var["act_bits"], var.get("rot", 0), var.get("asym", False)
+    ws = (qc.qlinear_asym_workspace_t if asym else qc.qlinear_workspace_t)(M, maxK, maxN)
     Y = torch.empty(M * maxN, dtype=torch.bfloat16, device="cuda")
     for i, c in enumerate(cases):
         key = (c.K, c.post_gelu, c.outliers)
         if key not in x_cache:
             x_cache[key] = to_dev_bf16(c.x())
-        layers.append(Layer(c, x_cache[key], ws, Y, layer_index=i))
+        layers.append(Layer(c, x_cache[key], ws, Y, layer_index=i, rot=rot, asym=asym))
     w4_layers = sum(c.bits == 4 for c in cases)
 
     cur_h, prev_h = synth.latent_pair(seed=0)
@@ -186,20 +207,42 @@ def main():
 
     def qlinear(L):
         c = L.case
-        check(qc.qc_qlinear(L.x.data_ptr(), qc.QC_BF16, c.M, c.K, L.pw.blob.data_ptr(),
-                            L.pw.scale.data_ptr(), c.bits, c.N, L.bias.data_ptr(), L.epi,
-                            L.Y.data_ptr(), qc.QC_OUT_BF16, L.ws.data_ptr(), L.ws.numel(), stream))
+        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16,
+                L.ws.data_ptr(), L.ws.numel(), stream)
+        head = (L.x.data_ptr(), qc.QC_BF16, c.M, c.K)
+        if asym:
+            check(qc.qc_qlinear_asym(*head, act_bits, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
+                                     L.row_sums.data_ptr(), *tail))
+        elif rot:
+            check(qc.qc_qlinear_rot(*head, act_bits, rot, L.pw.blob.data_ptr(),
+                                    L.pw.scale.data_ptr(), *tail))
+        elif act_bits != 8:
+            check(qc.qc_qlinear_act_bits(*head, act_bits, L.pw.blob.data_ptr(),
+                                         L.pw.scale.data_ptr(), *tail))
+        else:
+            check(qc.qc_qlinear(*head, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
 
     def quant_stage(L):
         c = L.case
-        check(qc.qc_qlinear_quant(L.x.data_ptr(), qc.QC_BF16, c.M, c.K, L.ws.data_ptr(),
-                                  L.ws.numel(), stream))
+        head = (L.x.data_ptr(), qc.QC_BF16, c.M, c.K)
+        tail = (L.ws.data_ptr(), L.ws.numel(), stream)
+        if asym:
+            check(qc.qc_qlinear_asym_quant(*head, act_bits, *tail))
+        elif rot:
+            check(qc.qc_qlinear_quant_rot(*head, act_bits, rot, *tail))
+        else:
+            check(qc.qc_qlinear_quant_bits(*head, act_bits, *tail))
 
     def gemm_stage(L):
         c = L.case
-        check(qc.qc_qlinear_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K, L.pw.blob.data_ptr(),
-                                 L.pw.scale.data_ptr(), c.bits, c.N, L.bias.data_ptr(), L.epi,
-                                 L.Y.data_ptr(), qc.QC_OUT_BF16, stream))
+        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16, stream)
+        if asym:
+            check(qc.qc_qlinear_asym_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
+                                          L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
+                                          L.row_sums.data_ptr(), *tail))
+        else:
+            check(qc.qc_qlinear_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
+                                     L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
 
     def delta_stage(on=None):
         check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
@@ -207,8 +250,12 @@ def main():
 
     def pack_stage(L):
         c = L.case
-        check(qc.qc_pack_weight(L.W.data_ptr(), c.N, c.K, c.bits, L.pw.blob.data_ptr(),
-                                L.pw.scale.data_ptr(), stream))
+        if rot:
+            check(qc.qc_pack_weight_rot(L.W.data_ptr(), c.N, c.K, c.bits, rot,
+                                        L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), stream))
+        else:
+            check(qc.qc_pack_weight(L.W.data_ptr(), c.N, c.K, c.bits, L.pw.blob.data_ptr(),
+                                    L.pw.scale.data_ptr(), stream))
 
     def step():
         for L in layers:
@@ -251,7 +298,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {})
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}) if args.variant == "a8" else {}
     gemm_us = per["gemm"]["avg_us"]
     gemm_tops = ops / (gemm_us * 1e-6) / 1e12
     quant_bytes = sum(c.M * c.K * 3 + 4 * c.M for c in cases)
@@ -273,7 +320,12 @@ def main():
         "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; bf16 in/out, fp32 scales)",
         "data": "synthetic",
-        "config": {"workload": describe, "name": args.workload, "layers": len(cases),
+        "config": {"workload": describe, "name": args.workload, "variant": args.variant,
+                   "activation_quantizer": {"a8": "symmetric int8 per token", "a6": "symmetric 6 bit per token",
+                                            "a4": "symmetric 4 bit per token",
+                                            "rot128": "Walsh-Hadamard blocks of 128 columns, then symmetric int8 per token",
+                                            "asym": "asymmetric uint8 per token with zero point"}[args.variant],
+                   "layers": len(cases),
                    "w4_layers": w4_layers, "M": M, "seed": cases[0].seed,
                    "offline_not_in_step": "qc_pack_weight",
                    "streams": "qc_qlinear on the current stream" +
@@ -306,7 +358,7 @@ def main():
                     "Infinity Cache between calls (warm)",
             "traffic": traffic.get("delta")}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cases[0])
+        result["cpu_baseline"] = cpu_baseline(cases[0], act_bits, rot, asym)
     print(json.dumps(result))
     return 0
 

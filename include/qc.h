@@ -209,6 +209,8 @@ qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int 
  *                        qc_qlinear_asym_workspace_bytes(M, K, N) bytes.  With QC_OUT_I32_ACC, Y
  *                        is sum_k (q[m, k] - 2^(act_bits-1)) qw[n, k], the sum the MFMA loop
  *                        forms on the stored bytes.
+ *   qc_qlinear_asym_quant, qc_qlinear_asym_gemm   the two halves of qc_qlinear_asym as calls
+ *                        of their own, as qc_qlinear_quant / qc_qlinear_gemm are of qc_qlinear.
  *   qc_debug_workspace_act_asym   test hook: the codes, scales and zero points
  *                        qc_qlinear_asym left in its workspace, in canonical form.
  * act_bits 8, 6 or 4.  K must be a multiple of 16 and at most 9216 (UNSUPPORTED otherwise).
@@ -222,6 +224,12 @@ qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K, int
                           const void *packed, const float *w_scale, const int32_t *w_row_sums,
                           int bits, int64_t N, const float *bias, qc_epilogue epi, void *Y,
                           qc_out ydt, void *workspace, size_t workspace_bytes, void *stream);
+qc_status qc_qlinear_asym_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                                void *workspace, size_t workspace_bytes, void *stream);
+qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspace_bytes, int64_t M, int64_t K,
+                               const void *packed, const float *w_scale,
+                               const int32_t *w_row_sums, int bits, int64_t N, const float *bias,
+                               qc_epilogue epi, void *Y, qc_out ydt, void *stream);
 qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t M, int64_t K, int act_bits,
                                       uint8_t *qx, float *x_scale, float *x_zero, void *stream);
 

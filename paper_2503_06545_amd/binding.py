@@ -30,7 +30,8 @@ EXPORTS = (
     "qc_divergence_score", "qc_cache_interval", "qc_activation_bits", "qc_prune_probability",
     "qc_pack_weight_rot", "qc_quant_act_rot", "qc_qlinear_quant_rot", "qc_qlinear_rot",
     "qc_qlinear_asym_workspace_bytes", "qc_weight_row_sums", "qc_quant_act_asym",
-    "qc_qlinear_asym", "qc_debug_workspace_act_asym",
+    "qc_qlinear_asym", "qc_debug_workspace_act_asym", "qc_qlinear_asym_quant",
+    "qc_qlinear_asym_gemm",
 )
 
 
@@ -98,6 +99,10 @@ def lib() -> ctypes.CDLL:
         L.qc_qlinear_asym.restype = i32
         L.qc_qlinear_asym.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp, i32, i64, vp, i32, vp, i32,
                                       vp, sz, vp]
+        L.qc_qlinear_asym_quant.restype = i32
+        L.qc_qlinear_asym_quant.argtypes = [vp, i32, i64, i64, i32, vp, sz, vp]
+        L.qc_qlinear_asym_gemm.restype = i32
+        L.qc_qlinear_asym_gemm.argtypes = [vp, sz, i64, i64, vp, vp, vp, i32, i64, vp, i32, vp, i32, vp]
         L.qc_debug_workspace_act_asym.restype = i32
         L.qc_debug_workspace_act_asym.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.qc_pack_weight_rot.restype = i32
@@ -248,6 +253,17 @@ def qc_qlinear_asym(X, xdt, M, K, act_bits, packed, w_scale, w_row_sums, bits, N
                     workspace, workspace_bytes, stream=0) -> int:
     return int(lib().qc_qlinear_asym(X, xdt, M, K, act_bits, packed, w_scale, w_row_sums, bits, N,
                                      bias, epi, Y, ydt, workspace, workspace_bytes, stream))
+
+
+def qc_qlinear_asym_quant(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_asym_quant(X, xdt, M, K, act_bits, workspace, workspace_bytes,
+                                           stream))
+
+
+def qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale, w_row_sums, bits, N,
+                         bias, epi, Y, ydt, stream=0) -> int:
+    return int(lib().qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale,
+                                          w_row_sums, bits, N, bias, epi, Y, ydt, stream))
 
 
 def qc_debug_workspace_act_asym(workspace, M, K, act_bits, qx, x_scale, x_zero, stream=0) -> int:

@@ -232,11 +232,53 @@ extern "C" qc_status qc_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, i
     return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }
 
+extern "C" qc_status qc_qlinear_asym_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                           int act_bits, void *workspace, size_t workspace_bytes,
+                                           void *stream) {
+    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (!quant_vector_path(K) || (M + 7) / 8 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    const ActWorkspaceAsym ws = act_workspace_asym(M, K);
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    uint8_t *base = (uint8_t *)workspace;
+    hipError_t e = launch_quant_act_asym(X, xdt, M, K, nullptr, base + ws.codes_offset, ws.sym.KF,
+                                         (float *)base, (float *)(base + ws.corr_offset), act_bits,
+                                         true, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
+                                          int64_t K, const void *packed, const float *w_scale,
+                                          const int32_t *w_row_sums, int bits, int64_t N,
+                                          const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                                          void *stream) {
+    if (!packed || !w_scale || !w_row_sums || !Y || !workspace || M < 1 || K < 1 || N < 1)
+        return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(w_row_sums, 16) ||
+        !aligned(Y, 16) || !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    if (qc_packed_weight_bytes(N, K, bits) == 0 || !quant_vector_path(K)) return QC_ERR_UNSUPPORTED;
+    const ActWorkspaceAsym ws = act_workspace_asym(M, K);
+    if ((ws.sym.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    const uint8_t *base = (const uint8_t *)workspace;
+    hipError_t e = launch_gemm(base + ws.codes_offset, (const float *)base, (const uint8_t *)packed,
+                               w_scale, bias, Y, M, N, K, bits, epi, ydt,
+                               (const float *)(base + ws.corr_offset), w_row_sums,
+                               (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
 extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                      int act_bits, const void *packed, const float *w_scale,
                                      const int32_t *w_row_sums, int bits, int64_t N,
                                      const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                                      void *workspace, size_t workspace_bytes, void *stream) {
+    // every argument is checked before the first launch, so a failed call has no side effect
     if (!X || !packed || !w_scale || !w_row_sums || !Y || !workspace || M < 1 || K < 1 || N < 1)
         return QC_ERR_INVALID_ARG;
     if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
@@ -252,13 +294,8 @@ extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int
     const ActWorkspaceAsym ws = act_workspace_asym(M, K);
     if ((ws.sym.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    uint8_t *base = (uint8_t *)workspace;
-    hipError_t e = launch_quant_act_asym(X, xdt, M, K, nullptr, base + ws.codes_offset, ws.sym.KF,
-                                         (float *)base, (float *)(base + ws.corr_offset), act_bits,
-                                         true, (hipStream_t)stream);
-    if (e != hipSuccess) return QC_ERR_DEVICE;
-    e = launch_gemm(base + ws.codes_offset, (const float *)base, (const uint8_t *)packed, w_scale,
-                    bias, Y, M, N, K, bits, epi, ydt, (const float *)(base + ws.corr_offset),
-                    w_row_sums, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    qc_status st = qc_qlinear_asym_quant(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream);
+    if (st != QC_OK) return st;
+    return qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale, w_row_sums, bits,
+                                N, bias, epi, Y, ydt, stream);
 }

@@ -100,6 +100,12 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_qlinear_asym(A, qc.QC_BF16, 4, 1144, 8, A, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
                               qc.QC_OUT_BF16, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
     assert qc.qc_debug_workspace_act_asym(A, 4, 1152, 7, A, A, A) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_qlinear_asym_quant(A, qc.QC_BF16, 4, 1152, 8, A, 64) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_qlinear_asym_quant(A, qc.QC_BF16, 4, 1152, 3, A, 1 << 30) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_qlinear_asym_gemm(A, 1 << 30, 4, 1152, A, A, None, 8, 8, None, qc.QC_EPI_NONE, A,
+                                   qc.QC_OUT_BF16) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_qlinear_asym_gemm(A, 64, 4, 1152, A, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
+                                   qc.QC_OUT_BF16) == qc.QC_ERR_WORKSPACE
     assert qc.qc_qlinear_asym_workspace_bytes(300, 100, 7) == 2 * 512 * 4 + 512 * 192
     # rotation: block sizes, divisibility, the K limit of the vector path
     assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 0, A, A) == qc.QC_ERR_UNSUPPORTED
