@@ -220,6 +220,29 @@ def test_qlinear_many_tiles_full_comparison(bits, M, N):
         run_asym_case(x, W, b, bits, "none", "f32", act_bits=6)
 
 
+def test_qlinear_seeded_random_shapes():
+    """Thirty shapes drawn from a seeded generator: any M, N, even K, every combination of input
+    type, weight bits, activation bits, epilogue and output type gets hit; full comparison."""
+    rng = np.random.default_rng(20250306)
+    for case in range(30):
+        M = int(rng.integers(1, 700))
+        K = 2 * int(rng.integers(1, 400))
+        N = int(rng.integers(1, 400))
+        bits = int(rng.choice([8, 4]))
+        act_bits = int(rng.choice([8, 8, 6, 4]))
+        epi = str(rng.choice(["none", "gelu_tanh", "gelu_erf"]))
+        out = str(rng.choice(["f32", "bf16"]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        x = random_x(rng, M, K, dtype)
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float32) if case % 3 else None
+        try:
+            run_linear_case(x, W, b, bits, epi, out, act_bits=act_bits)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: M={M} K={K} N={N} bits={bits} act_bits={act_bits} "
+                                 f"epi={epi} out={out} x={dtype}: {e}") from e
+
+
 def test_qlinear_closed_form_integers_and_extremes():
     """Integer operands with unit scales reproduce X W^T + b exactly; all-127 operands reach the
     largest accumulator magnitude at K = 4608."""
