@@ -45,14 +45,19 @@ __global__ __launch_bounds__(256) void read_kernel(const float4 *__restrict__ a,
 
 // ---- MFMA with optional operand traffic -----------------------------------------------------
 // per iteration: 16 MFMAs (2 x 8 tiles); LDSR ds_read_b128 per wavefront from LDS; GLD 16 B/lane
-// global loads per wavefront from an L2-resident buffer
-template <int LDSR, int GLD>
+// global loads per wavefront from an L2-resident buffer.  VIA_LDS: those GLD loads are
+// direct-to-LDS copies into a ring private to the wavefront, each followed by a ds_read_b128 of
+// the same size (the reads race with the copies on purpose: only the traffic matters here).
+template <int LDSR, int GLD, bool VIA_LDS = false>
 __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ data,
                                                       const uint8_t *__restrict__ gsrc, int iters,
                                                       int *out) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[16384];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[16384 + 32768];
     for (int i = threadIdx.x; i < 16384 / 16; i += 256) ((v4i *)lds)[i] = data[i];
+    for (int i = threadIdx.x; i < 32768 / 16; i += 256) ((v4i *)(lds + 16384))[i] = data[i & 1023];
     __syncthreads();
+    uint8_t *ring = lds + 16384 + (threadIdx.x >> 6) * 8192;  // 8 slots of 1 KiB per wavefront
+    const uint32_t ring_lane = (uint32_t)(uintptr_t)ring + (threadIdx.x & 63) * 16;
     v16i acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -69,7 +74,18 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
     for (int it = 0; it < iters; ++it) {
         v4i gl[GLD > 0 ? GLD : 1];
 #pragma unroll
-        for (int j = 0; j < GLD; ++j) gl[j] = *(const v4i *)(g + ((it * GLD + j) & 15) * 1024);
+        for (int j = 0; j < GLD; ++j) {
+            const uint8_t *src = g + ((it * GLD + j) & 15) * 1024;
+            if (VIA_LDS) {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)src,
+                    (__attribute__((address_space(3))) void *)(ring + ((it * GLD + j) & 7) * 1024), 16, 0, 0);
+                asm volatile("ds_read_b128 %0, %1" : "=v"(gl[j])
+                             : "v"(ring_lane + (uint32_t)(((it * GLD + j + 4) & 7) * 1024)));
+            } else {
+                gl[j] = *(const v4i *)src;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < LDSR; ++j) {
             const v4i v = *(const v4i *)(lds + ((j + it) & 15) * 1024 + lane * 16);
@@ -81,9 +97,11 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
 #pragma unroll
             for (int t = 0; t < 8; ++t)
                 acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[t], acc[t], 0, 0, 0);
+        if (VIA_LDS) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
         for (int j = 0; j < GLD; ++j) gx ^= gl[j];
     }
+    if (VIA_LDS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int s = gx[0] ^ gx[1] ^ gx[2] ^ gx[3];
 #pragma unroll
     for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
@@ -231,6 +249,8 @@ int main() {
            tops(settled_ms([&] { mfma_kernel<8, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
     printf("mfma random operands + 256 B per MFMA loaded from L2:                          %5.0f TOPS\n",
            tops(settled_ms([&] { mfma_kernel<0, 4><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma random operands + 256 B per MFMA copied L2 -> LDS and read back from LDS:  %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma_kernel<0, 4, true><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
     printf("mfma random operands + 0.5 ds_read_b128 and 384 B from L2 per MFMA (the GEMM): %5.0f TOPS\n",
            tops(settled_ms([&] { mfma_kernel<8, 6><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
     printf("mfma random operands + 0.5 ds_read_b128 and 128 B from L2 per MFMA:            %5.0f TOPS\n",
