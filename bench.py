@@ -139,7 +139,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by token "
-              "rows without any exchange, see DESIGN.md", file=sys.stderr)
+              "rows without any exchange between GPUs", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -168,13 +168,13 @@ def main():
                  "fc2_512_w4": synth.FC2_512_W4}[args.workload]
         cases = [case0]
         describe = {
-            "qkv256": "STDiT QKV projection 256x256 (BASELINE configs[1]): X bf16 [16384,1152] "
+            "qkv256": "STDiT QKV projection 256x256, the headline configuration: X bf16 [16384,1152] "
                       "N(0,1) with 12 outlier columns x20, W8A8 [3456,1152], bias, bf16 out",
-            "fc1_512": "STDiT MLP fc1 + GELU(tanh) 512x512 (BASELINE configs[2]): X bf16 "
+            "fc1_512": "STDiT MLP fc1 + GELU(tanh) 512x512: X bf16 "
                        "[65536,1152], W8A8 [4608,1152], bf16 out",
-            "fc2_512_w8": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] "
+            "fc2_512_w8": "STDiT MLP fc2 512x512: X bf16 [65536,4608] "
                           "post-GELU, W8A8 [1152,4608], bf16 out",
-            "fc2_512_w4": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] "
+            "fc2_512_w4": "STDiT MLP fc2 512x512: X bf16 [65536,4608] "
                           "post-GELU, W4A8 [1152,4608] int4 weights, bf16 out",
         }[args.workload] + "; + latent delta on 2 x [16,4,16,64,64] fp32"
         scale = max(1, (case0.M * case0.N * case0.K) // (16384 * 3456 * 1152))
