@@ -15,6 +15,8 @@ Paper passages each function follows (arxiv 2503.06545):
   qlinear                   fused quantize / dequantize)
   latent_delta              Section 3.2 HLC, Eq. (5) numerator
   layer_similarity          Section 3.3 SRAP, Eq. (9)
+  quant_act_tensor,         Section 4.1 "Quantization Scheme" read literally: one activation
+  qlinear_tensor            scale per layer input (per tensor), computed online
   quant_act_asym,           Section 3.1 Eq. (3), Eq. (4) as printed: asymmetric, with a zero
   qlinear_asym              point per token
   rotate_rows, quant_act_   Section 3.2 AIGQ (1) (rotation against outlier channels) and
@@ -380,3 +382,22 @@ def qlinear_asym(X, qw, sw, bias=None, epi=EPI_NONE, act_bits: int = 8):
     _L().orc_qlinear_asym(_p(X), int(is_bf16), M, K, levels(act_bits), _p(qw), _p(sw), N,
                           _p(bias), int(epi), _p(qx), _p(sx), _p(zx), _p(y))
     return {"qx": qx, "sx": sx, "zx": zx, "y": y}
+
+
+# ---- one activation scale per layer input -----------------------------------------------------
+
+def quant_act_tensor(X, act_bits: int = 8):
+    """The symmetric quantizer with ONE scale for the whole activation tensor (the paper's
+    "dynamic per-layer activation quantization" taken literally): the tensor is quantized as a
+    single long row.  Returns (int8 codes [M, K], float32 scale)."""
+    M, K = X.shape
+    q, s = _quant_rows(np.ascontiguousarray(X).reshape(1, M * K), qmax(act_bits))
+    return q.reshape(M, K), np.float32(s[0])
+
+
+def qlinear_tensor(X, qw, sw, bias=None, epi=EPI_NONE, act_bits: int = 8):
+    """Quantized linear on per-tensor activation codes; dict(qx, sx, acc, y), sx a scalar."""
+    qx, s = quant_act_tensor(X, act_bits)
+    acc = gemm_i32(qx, qw)
+    y = epilogue(acc, np.full(X.shape[0], s, np.float32), sw, bias, epi)
+    return {"qx": qx, "sx": s, "acc": acc, "y": y}

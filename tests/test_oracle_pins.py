@@ -657,3 +657,38 @@ def test_asymmetric_linear_is_the_product_of_dequantized_operands_and_gains_a_bi
     rg = oracle.qlinear_asym(X, qw, sw, b, oracle.EPI_GELU_ERF)["y"]
     rn = oracle.qlinear_asym(X, qw, sw, b, oracle.EPI_NONE)["y"]
     assert np.allclose(rg, [[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row] for row in rn], rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------ one activation scale per layer input
+
+def test_per_tensor_quantizer_is_the_row_quantizer_with_the_largest_scale():
+    rng = np.random.default_rng(97)
+    X = rng.standard_normal((9, 64)).astype(np.float32)
+    X[4, 7] = 30.0
+    for bits in (8, 6, 4):
+        q, s = oracle.quant_act_tensor(X, bits)
+        _, s_rows = oracle.quant_act(X, bits)
+        assert s == s_rows.max() and s == np.float32(30.0) / np.float32(oracle.qmax(bits))
+        # every element is rounded against that one scale: exact rational check
+        want, cs = exact_quant_row(X.reshape(-1), oracle.qmax(bits))
+        assert cs == float(s) and np.array_equal(q.reshape(-1), want)
+        # the row that holds the maximum gets the codes its own scale would give
+        assert np.array_equal(q[4], oracle.quant_act(X[4:5], bits)[0][0])
+    # rows with equal absmax: per tensor and per token coincide
+    Y = rng.standard_normal((5, 32)).astype(np.float32)
+    Y[:, 0] = 4.0
+    Y = np.clip(Y, -4, 4)
+    qt, st = oracle.quant_act_tensor(Y)
+    qr, sr = oracle.quant_act(Y)
+    assert np.array_equal(qt, qr) and np.all(sr == st)
+    # the linear: product of dequantized operands
+    W = (0.02 * rng.standard_normal((7, 64))).astype(np.float32)
+    b = (0.01 * rng.standard_normal(7)).astype(np.float32)
+    qw, sw = oracle.quant_weight(W, 8)
+    r = oracle.qlinear_tensor(X, qw, sw, b)
+    xhat = float(r["sx"]) * r["qx"].astype(np.float64)
+    what = sw.astype(np.float64)[:, None] * qw.astype(np.float64)
+    assert np.allclose(r["y"], xhat @ what.T + b, rtol=1e-12, atol=1e-15)
+    from paper_2503_06545_amd import synth
+    Xb = synth.to_bf16_bits(X)
+    assert np.array_equal(oracle.quant_act_tensor(Xb)[0], oracle.quant_act_tensor(oracle.widen_f32(Xb))[0])
