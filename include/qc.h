@@ -233,6 +233,30 @@ qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspace_bytes, in
 qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t M, int64_t K, int act_bits,
                                       uint8_t *qx, float *x_scale, float *x_zero, void *stream);
 
+/* ---- one activation scale per layer input ----------------------------------------------------
+ * Section 4.1 "Quantization Scheme" speaks of dynamic per-layer activation quantization with
+ * parameters computed online.  The calls above take the finer reading (one scale per token);
+ * these take the sentence literally: ONE scale for the whole activation tensor X [M, K],
+ *      s = max(max_{m,k} |X[m,k]|, 2^-64) / qmax,   q = clamp(rne(X / s), -qmax, qmax),
+ * computed online by a reduction over X before the cast (X is read twice).
+ *   qc_quant_act_tensor   qx int8 [M, K] row major, x_scale float [1]; workspace >=
+ *                         qc_quant_act_tensor_workspace_bytes(M, K) bytes (slab maxima)
+ *   qc_qlinear_tensor     quantize + GEMM + epilogue as qc_qlinear_act_bits; workspace >=
+ *                         qc_qlinear_tensor_workspace_bytes(M, K, N) bytes, 256-byte aligned.  Its
+ *                         first part has the layout of qc_qlinear's workspace (the scale is
+ *                         repeated per token), so qc_qlinear_gemm and qc_debug_workspace_act
+ *                         work on it.
+ * Deterministic.  Errors as for the per-token calls. */
+size_t qc_quant_act_tensor_workspace_bytes(int64_t M, int64_t K);
+qc_status qc_quant_act_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                              int8_t *qx, float *x_scale, void *workspace, size_t workspace_bytes,
+                              void *stream);
+size_t qc_qlinear_tensor_workspace_bytes(int64_t M, int64_t K, int64_t N);
+qc_status qc_qlinear_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
+                            const void *packed, const float *w_scale, int bits, int64_t N,
+                            const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test hook: after qc_qlinear(.., M, K, .., workspace, ..) returned QC_OK, copy the
  * activation codes and scales it used out of the workspace in canonical order:
  * qx int8 [M, K] row major, x_scale float [M]. */

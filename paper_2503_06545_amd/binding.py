@@ -31,7 +31,8 @@ EXPORTS = (
     "qc_pack_weight_rot", "qc_quant_act_rot", "qc_qlinear_quant_rot", "qc_qlinear_rot",
     "qc_qlinear_asym_workspace_bytes", "qc_weight_row_sums", "qc_quant_act_asym",
     "qc_qlinear_asym", "qc_debug_workspace_act_asym", "qc_qlinear_asym_quant",
-    "qc_qlinear_asym_gemm",
+    "qc_qlinear_asym_gemm", "qc_quant_act_tensor_workspace_bytes", "qc_quant_act_tensor",
+    "qc_qlinear_tensor_workspace_bytes", "qc_qlinear_tensor",
 )
 
 
@@ -103,6 +104,15 @@ def lib() -> ctypes.CDLL:
         L.qc_qlinear_asym_quant.argtypes = [vp, i32, i64, i64, i32, vp, sz, vp]
         L.qc_qlinear_asym_gemm.restype = i32
         L.qc_qlinear_asym_gemm.argtypes = [vp, sz, i64, i64, vp, vp, vp, i32, i64, vp, i32, vp, i32, vp]
+        L.qc_quant_act_tensor_workspace_bytes.restype = sz
+        L.qc_quant_act_tensor_workspace_bytes.argtypes = [i64, i64]
+        L.qc_quant_act_tensor.restype = i32
+        L.qc_quant_act_tensor.argtypes = [vp, i32, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.qc_qlinear_tensor_workspace_bytes.restype = sz
+        L.qc_qlinear_tensor_workspace_bytes.argtypes = [i64, i64, i64]
+        L.qc_qlinear_tensor.restype = i32
+        L.qc_qlinear_tensor.argtypes = [vp, i32, i64, i64, i32, vp, vp, i32, i64, vp, i32, vp, i32, vp,
+                                        sz, vp]
         L.qc_debug_workspace_act_asym.restype = i32
         L.qc_debug_workspace_act_asym.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.qc_pack_weight_rot.restype = i32
@@ -264,6 +274,26 @@ def qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale, w_ro
                          bias, epi, Y, ydt, stream=0) -> int:
     return int(lib().qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale,
                                           w_row_sums, bits, N, bias, epi, Y, ydt, stream))
+
+
+def qc_quant_act_tensor_workspace_bytes(M: int, K: int) -> int:
+    return int(lib().qc_quant_act_tensor_workspace_bytes(M, K))
+
+
+def qc_quant_act_tensor(X, xdt, M, K, act_bits, qx, x_scale, workspace, workspace_bytes,
+                        stream=0) -> int:
+    return int(lib().qc_quant_act_tensor(X, xdt, M, K, act_bits, qx, x_scale, workspace,
+                                         workspace_bytes, stream))
+
+
+def qc_qlinear_tensor_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().qc_qlinear_tensor_workspace_bytes(M, K, N))
+
+
+def qc_qlinear_tensor(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                      workspace, workspace_bytes, stream=0) -> int:
+    return int(lib().qc_qlinear_tensor(X, xdt, M, K, act_bits, packed, w_scale, bits, N, bias, epi,
+                                       Y, ydt, workspace, workspace_bytes, stream))
 
 
 def qc_debug_workspace_act_asym(workspace, M, K, act_bits, qx, x_scale, x_zero, stream=0) -> int:
@@ -555,3 +585,43 @@ def debug_workspace_act_asym_t(workspace, M: int, K: int, act_bits: int = 8):
                                        sx.data_ptr(), zx.data_ptr(), _stream()),
            "qc_debug_workspace_act_asym")
     return qx, sx, zx
+
+
+# ---- one activation scale per layer input -------------------------------------------------------
+
+def quant_act_tensor_t(X, act_bits: int = 8):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2
+    M, K = X.shape
+    qx = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    sx = torch.empty(1, dtype=torch.float32, device=X.device)
+    ws = torch.empty(qc_quant_act_tensor_workspace_bytes(M, K), dtype=torch.uint8, device=X.device)
+    _check(qc_quant_act_tensor(X.data_ptr(), _xdt(X), M, K, act_bits, qx.data_ptr(), sx.data_ptr(),
+                               ws.data_ptr(), ws.numel(), _stream()), "qc_quant_act_tensor")
+    return qx, sx
+
+
+def qlinear_tensor_workspace_t(M: int, K: int, N: int, device="cuda"):
+    torch = _torch()
+    nbytes = qc_qlinear_tensor_workspace_bytes(M, K, N)
+    if nbytes == 0:
+        raise QcError(QC_ERR_UNSUPPORTED, "qc_qlinear_tensor_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def qlinear_tensor_t(X, pw: PackedWeight, bias=None, epi="none", out="bf16", workspace=None, Y=None,
+                     act_bits: int = 8):
+    torch = _torch()
+    assert X.is_cuda and X.is_contiguous() and X.dim() == 2 and X.shape[1] == pw.K
+    M, K = X.shape
+    if workspace is None:
+        workspace = qlinear_tensor_workspace_t(M, K, pw.N, X.device)
+    if Y is None:
+        ydtype = {"f32": torch.float32, "bf16": torch.bfloat16, "i32": torch.int32}[out]
+        Y = torch.empty((M, pw.N), dtype=ydtype, device=X.device)
+    _check(qc_qlinear_tensor(X.data_ptr(), _xdt(X), M, K, act_bits, pw.blob.data_ptr(),
+                             pw.scale.data_ptr(), pw.bits, pw.N,
+                             None if bias is None else bias.data_ptr(), EPI[epi], Y.data_ptr(),
+                             OUT[out], workspace.data_ptr(), workspace.numel(), _stream()),
+           "qc_qlinear_tensor")
+    return Y

@@ -299,3 +299,60 @@ extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int
     return qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale, w_row_sums, bits,
                                 N, bias, epi, Y, ydt, stream);
 }
+
+// ---- one activation scale per layer input (Section 4.1 "Quantization Scheme") ------------------
+
+extern "C" size_t qc_quant_act_tensor_workspace_bytes(int64_t M, int64_t K) {
+    if (M < 1 || K < 1 || K > QC_MAX_K) return 0;
+    return tensor_partials_bytes();
+}
+
+extern "C" qc_status qc_quant_act_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                         int act_bits, int8_t *qx, float *x_scale, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
+    if (!X || !qx || !x_scale || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4) || !aligned(workspace, 256))
+        return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < tensor_partials_bytes()) return QC_ERR_WORKSPACE;
+    hipError_t e = launch_quant_act_tensor(X, xdt, M, K, qx, nullptr, 0, x_scale, true,
+                                           (float *)workspace, act_bits, (hipStream_t)stream);
+    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+extern "C" size_t qc_qlinear_tensor_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (M < 1 || K < 1 || N < 1 || K > QC_MAX_K) return 0;
+    return act_workspace(M, K).total_bytes + tensor_partials_bytes();
+}
+
+extern "C" qc_status qc_qlinear_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                       int act_bits, const void *packed, const float *w_scale,
+                                       int bits, int64_t N, const float *bias, qc_epilogue epi,
+                                       void *Y, qc_out ydt, void *workspace, size_t workspace_bytes,
+                                       void *stream) {
+    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
+        return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
+        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    const ActWorkspace ws = act_workspace(M, K);
+    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (workspace_bytes < ws.total_bytes + tensor_partials_bytes()) return QC_ERR_WORKSPACE;
+    // [ the workspace of qc_qlinear ][ slab maxima ]: the first part is what qc_qlinear_gemm and
+    // qc_debug_workspace_act read, with the one scale repeated for every token
+    uint8_t *base = (uint8_t *)workspace;
+    hipError_t e = launch_quant_act_tensor(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
+                                           (float *)base, false, (float *)(base + ws.total_bytes),
+                                           act_bits, (hipStream_t)stream);
+    if (e != hipSuccess) return QC_ERR_DEVICE;
+    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
+                           ydt, stream);
+}

@@ -72,6 +72,14 @@ hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, i
                             uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
                             int rot_block, hipStream_t stream);
 bool quant_rotation_supported(int64_t K, int rot_block);
+// One scale for the whole tensor: a slab-wise absmax launch into `partials`
+// (tensor_partials_bytes() bytes), then the row kernels with that absmax.  single_scale: write
+// x_scale[0] only; otherwise x_scale[m] gets the same value for every row (what the GEMM reads).
+size_t tensor_partials_bytes();
+hipError_t launch_quant_act_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                   int8_t *qx_rowmajor, uint8_t *qx_tiled, int64_t KF,
+                                   float *x_scale, bool single_scale, float *partials, int act_bits,
+                                   hipStream_t stream);
 // K the vector quantization kernels take: a multiple of 16, at most 9216
 bool quant_vector_path(int64_t K);
 // Asymmetric codes (Section 3.1 Eq. (3)-(4) as printed).  shifted = false: canonical unsigned

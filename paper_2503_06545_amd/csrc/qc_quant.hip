@@ -93,6 +93,64 @@ __device__ inline uint32_t codes4(float q0, float q1, float q2, float q3, float 
 
 __device__ inline float scale_of(float absmax, float qmax) { return fmaxf(absmax, kAbsmaxFloor) / qmax; }
 
+// One scale for a whole activation tensor (Section 4.1 "Quantization Scheme": activation
+// quantization per layer, parameters computed online): a first launch leaves the absmax of up to
+// 256 slabs of the tensor in `partials`; every wavefront of the quantization kernel combines
+// them itself (max is exact in any order), which needs neither atomics nor a third launch.
+struct TensorMax {
+    const float *partials;  // nullptr: one scale per row
+    int count;
+    bool single_scale;      // write x_scale[0] only, not one (equal) value per row
+};
+
+__device__ inline float tensor_absmax(const TensorMax &t, int lane) {
+    float a = 0.0f;
+    for (int j = lane; j < t.count; j += 64) a = fmaxf(a, t.partials[j]);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    return a;
+}
+
+constexpr int kSlabThreads = 256;
+constexpr int kMaxSlabs = 256;
+
+template <typename XT>
+__global__ __launch_bounds__(kSlabThreads) void tensor_absmax_kernel(const XT *__restrict__ X, int64_t n,
+                                                                    float *__restrict__ partials) {
+    __shared__ float wave_max[kSlabThreads / 64];
+    constexpr int kPer = 16 / (int)sizeof(XT);  // elements per 16 B load
+    const int64_t nv = n / kPer;
+    const int64_t stride = (int64_t)gridDim.x * kSlabThreads;
+    float a = 0.0f;
+    for (int64_t i = (int64_t)blockIdx.x * kSlabThreads + threadIdx.x; i < nv; i += stride) {
+        const uint4 v = reinterpret_cast<const uint4 *>(X)[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (sizeof(XT) == 2) {
+                a = fmaxf(a, fabsf(bf16_lo(w[j])));
+                a = fmaxf(a, fabsf(bf16_hi(w[j])));
+            } else {
+                a = fmaxf(a, fabsf(__uint_as_float(w[j])));
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (int)(n - nv * kPer)) {  // trailing elements
+        const XT t = X[nv * kPer + threadIdx.x];
+        if constexpr (sizeof(XT) == 2) a = fmaxf(a, fabsf(__uint_as_float((uint32_t)t << 16)));
+        else a = fmaxf(a, fabsf(t));
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kSlabThreads / 64; ++w) a = fmaxf(a, wave_max[w]);
+        partials[blockIdx.x] = a;
+    }
+}
+
 // 8 lanes share a row and a wavefront holds 8 rows x 1152 columns (72 units of 16, 9 per lane)
 // in registers, so that every 16 B store of the fragment layout completes a 128 B line (8 rows
 // x 16 B) within one instruction.  Longer rows are cut into column slices of 1152, one
@@ -106,7 +164,8 @@ constexpr int kMaxSlices = 8;
 template <typename XT>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
-    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax) {
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax,
+    TensorMax tmax) {
     __shared__ float slice_max[kMaxSlices][kRowsPerBlock];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6, slices = blockDim.x >> 6;
     const int sub = lane % kLanesPerRow, row_in_block = lane / kLanesPerRow;
@@ -124,21 +183,29 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     }
 
     float a = 0.0f;
+    if (tmax.partials) {  // one scale for the whole tensor: its absmax was reduced beforehand
+        a = tensor_absmax(tmax, lane);
+    } else {
 #pragma unroll
-    for (int i = 0; i < kUnitsPerThread; ++i)
+        for (int i = 0; i < kUnitsPerThread; ++i)
 #pragma unroll
-        for (int e = 0; e < kUnit; ++e) a = fmaxf(a, fabsf(u[i].get(e)));
+            for (int e = 0; e < kUnit; ++e) a = fmaxf(a, fabsf(u[i].get(e)));
 #pragma unroll
-    for (int d = 1; d < kLanesPerRow; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
-    if (slices > 1) {  // uniform over the block
-        if (sub == 0) slice_max[slice][row_in_block] = a;
-        __syncthreads();
-        for (int sl = 0; sl < slices; ++sl) a = fmaxf(a, slice_max[sl][row_in_block]);
+        for (int d = 1; d < kLanesPerRow; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+        if (slices > 1) {  // uniform over the block
+            if (sub == 0) slice_max[slice][row_in_block] = a;
+            __syncthreads();
+            for (int sl = 0; sl < slices; ++sl) a = fmaxf(a, slice_max[sl][row_in_block]);
+        }
     }
 
     const float s = scale_of(a, qmax);
     const float r = 1.0f / s;  // correctly rounded
-    if (live && sub == 0 && slice == 0) x_scale[row] = s;
+    if (tmax.single_scale) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) x_scale[0] = s;
+    } else if (live && sub == 0 && slice == 0) {
+        x_scale[row] = s;
+    }
     if (!live) return;
 
     int8_t *out_rows = qx ? qx + row * K : nullptr;
@@ -367,7 +434,8 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
 template <typename XT>
 __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
-    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax) {
+    uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax,
+    TensorMax tmax) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * (kGenericThreads / 64) + (threadIdx.x >> 6);
     if (row >= M) return;
@@ -377,11 +445,19 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
         else return v;
     };
     float a = 0.0f;
-    for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(widen(xrow[k])));
+    if (tmax.partials) {
+        a = tensor_absmax(tmax, lane);
+    } else {
+        for (int64_t k = lane; k < K; k += 64) a = fmaxf(a, fabsf(widen(xrow[k])));
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+        for (int d = 1; d < 64; d <<= 1) a = fmaxf(a, __shfl_xor(a, d));
+    }
     const float s = scale_of(a, qmax);
-    if (lane == 0) x_scale[row] = s;
+    if (tmax.single_scale) {
+        if (row == 0 && lane == 0) x_scale[0] = s;
+    } else if (lane == 0) {
+        x_scale[row] = s;
+    }
     for (int64_t k = lane; k < K; k += 64) {
         const int8_t c = (int8_t)quant_code(widen(xrow[k]), s, qmax);
         if (qx) qx[row * K + k] = c;
@@ -391,7 +467,8 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
 
 template <typename XT>
 hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
-                        int64_t KF, float *x_scale, float qmax, int rot, hipStream_t stream) {
+                        int64_t KF, float *x_scale, float qmax, int rot, TensorMax tmax,
+                        hipStream_t stream) {
     const int64_t units = K / kUnit;
     const int64_t slices = (units + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const bool vec = (K % kUnit == 0) && slices <= kMaxSlices;
@@ -405,12 +482,12 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
     if (!vec) {
         const int64_t blocks = (M + 3) / 4;
         quant_rows_generic_kernel<XT><<<dim3((unsigned)blocks), dim3(kGenericThreads), 0, stream>>>(
-            X, M, K, qx, qx_tiled, KF, x_scale, qmax);
+            X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
         return hipGetLastError();
     }
     const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
     quant_rows_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
-        X, M, K, qx, qx_tiled, KF, x_scale, qmax);
+        X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
     return hipGetLastError();
 }
 
@@ -445,11 +522,39 @@ hipError_t launch_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, i
                             uint8_t *qx_tiled, int64_t KF, float *x_scale, int act_bits,
                             int rot_block, hipStream_t stream) {
     const float qmax = (float)((1 << (act_bits - 1)) - 1);  // 127, 31 or 7 in an int8 container
+    const TensorMax per_row = {nullptr, 0, false};
     if (xdt == QC_BF16)
         return launch_typed<uint16_t>((const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale,
-                                      qmax, rot_block, stream);
+                                      qmax, rot_block, per_row, stream);
     return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, qmax,
-                               rot_block, stream);
+                               rot_block, per_row, stream);
+}
+
+size_t tensor_partials_bytes() { return (size_t)kMaxSlabs * sizeof(float); }
+
+hipError_t launch_quant_act_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                   int8_t *qx_rowmajor, uint8_t *qx_tiled, int64_t KF,
+                                   float *x_scale, bool single_scale, float *partials, int act_bits,
+                                   hipStream_t stream) {
+    const float qmax = (float)((1 << (act_bits - 1)) - 1);
+    const int64_t n = M * K;
+    const int per = xdt == QC_BF16 ? 8 : 4;
+    int64_t slabs = (n / per + (int64_t)kSlabThreads * 8 - 1) / ((int64_t)kSlabThreads * 8);
+    if (slabs < 1) slabs = 1;
+    if (slabs > kMaxSlabs) slabs = kMaxSlabs;
+    if (xdt == QC_BF16)
+        tensor_absmax_kernel<uint16_t><<<dim3((unsigned)slabs), dim3(kSlabThreads), 0, stream>>>(
+            (const uint16_t *)X, n, partials);
+    else
+        tensor_absmax_kernel<float><<<dim3((unsigned)slabs), dim3(kSlabThreads), 0, stream>>>(
+            (const float *)X, n, partials);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    const TensorMax tmax = {partials, (int)slabs, single_scale};
+    if (xdt == QC_BF16)
+        return launch_typed<uint16_t>((const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale,
+                                      qmax, 0, tmax, stream);
+    return launch_typed<float>((const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, qmax, 0,
+                               tmax, stream);
 }
 
 }  // namespace qc

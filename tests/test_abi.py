@@ -107,6 +107,16 @@ def test_argument_errors_come_before_any_launch():
     assert qc.qc_qlinear_asym_gemm(A, 64, 4, 1152, A, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
                                    qc.QC_OUT_BF16) == qc.QC_ERR_WORKSPACE
     assert qc.qc_qlinear_asym_workspace_bytes(300, 100, 7) == 2 * 512 * 4 + 512 * 192
+    # one scale per tensor
+    assert qc.qc_quant_act_tensor(A, qc.QC_BF16, 4, 16, 8, A, A, None, 1 << 20) == qc.QC_ERR_INVALID_ARG
+    assert qc.qc_quant_act_tensor(A, qc.QC_BF16, 4, 16, 5, A, A, A, 1 << 20) == qc.QC_ERR_UNSUPPORTED
+    assert qc.qc_quant_act_tensor(A, qc.QC_BF16, 4, 16, 8, A, A, A, 16) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_quant_act_tensor_workspace_bytes(4, 16) == 1024
+    assert qc.qc_qlinear_tensor_workspace_bytes(300, 100, 7) == 512 * 4 + 512 * 192 + 1024
+    assert qc.qc_qlinear_tensor(A, qc.QC_BF16, 4, 16, 8, A, A, 8, 8, None, qc.QC_EPI_NONE, A,
+                                qc.QC_OUT_BF16, A, qc.qc_qlinear_workspace_bytes(4, 16, 8)) == qc.QC_ERR_WORKSPACE
+    assert qc.qc_qlinear_tensor(A, qc.QC_BF16, 4, 16, 8, A, A, 8, 8, None, 7, A,
+                                qc.QC_OUT_BF16, A, 1 << 30) == qc.QC_ERR_INVALID_ARG
     # rotation: block sizes, divisibility, the K limit of the vector path
     assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 0, A, A) == qc.QC_ERR_UNSUPPORTED
     assert qc.qc_quant_act_rot(A, qc.QC_BF16, 4, 1152, 8, 48, A, A) == qc.QC_ERR_UNSUPPORTED

@@ -644,3 +644,41 @@ def test_qlinear_asym_gains_on_one_sided_input_and_is_exact_on_integers():
     y = host_f64(qc.qlinear_asym_t(dev(Xi - 100), pwi, qc.weight_row_sums_t(pwi), None, "none", "f32"))
     want = (Xi.astype(np.float64) - 100) @ Wi.astype(np.float64).T
     assert np.max(np.abs(y - want)) <= 2e-7 * np.max(np.abs(want)) * 4
+
+
+# ------------------------------------------------------------------ one scale per layer input
+
+@pytest.mark.parametrize("act_bits", [8, 6, 4])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K", [(256, 1152), (77, 4608), (1, 16), (9, 1000), (130, 7), (3, 10000),
+                                 (2048, 1152)])
+def test_quant_act_tensor_bit_exact(act_bits, dtype, M, K):
+    rng = np.random.default_rng(M * 17 + K + act_bits)
+    x = random_x(rng, M, K, dtype)
+    q_ref, s_ref = oracle.quant_act_tensor(x, act_bits)
+    qx, sx = qc.quant_act_tensor_t(dev(x), act_bits)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), np.array([s_ref], np.float32))
+    assert np.array_equal(qx.cpu().numpy(), q_ref)
+
+
+@pytest.mark.parametrize("bits,act_bits", [(8, 8), (4, 8), (4, 6)])
+@pytest.mark.parametrize("M,K,N", [(520, 1152, 300), (33, 200, 77), (700, 4608, 130)])
+def test_qlinear_tensor_matches_oracle(bits, act_bits, M, K, N):
+    rng = np.random.default_rng(M + K + N + bits + act_bits)
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    ref = oracle.qlinear_tensor(x, qw_ref, sw_ref, b, oracle.EPI_GELU_TANH, act_bits)
+    xd, pw = dev(x), qc.pack_weight_t(dev(W), bits)
+    ws = qc.qlinear_tensor_workspace_t(M, K, N)
+    y = qc.qlinear_tensor_t(xd, pw, dev(b), "gelu_tanh", "bf16", workspace=ws, act_bits=act_bits)
+    qx, sx = qc.debug_workspace_act_t(ws, M, K)
+    acc = qc.qlinear_tensor_t(xd, pw, None, "none", "i32", workspace=ws, act_bits=act_bits)
+    torch.cuda.synchronize()
+    assert bits_equal(sx.cpu().numpy(), np.full(M, ref["sx"], np.float32))
+    assert np.array_equal(qx.cpu().numpy(), ref["qx"])
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(ref["y"]))
+    assert_outputs_close(host_f64(y), y_ref, RTOL["bf16"])
