@@ -161,7 +161,10 @@ constexpr int kRowsPerBlock = 64 / kLanesPerRow;
 constexpr int kUnitsPerSlice = kLanesPerRow * kUnitsPerThread;  // 72 units = 1152 columns
 constexpr int kMaxSlices = 8;
 
-template <typename XT>
+// TENSOR: the absmax comes from `tmax` (one scale for the whole tensor).  A template parameter
+// rather than a test of tmax.partials, so that the per-token kernel is compiled exactly as if
+// the other did not exist.
+template <typename XT, bool TENSOR>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
     uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax,
@@ -183,7 +186,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     }
 
     float a = 0.0f;
-    if (tmax.partials) {  // one scale for the whole tensor: its absmax was reduced beforehand
+    if (TENSOR) {  // one scale for the whole tensor: its absmax was reduced beforehand
         a = tensor_absmax(tmax, lane);
     } else {
 #pragma unroll
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
 
     const float s = scale_of(a, qmax);
     const float r = 1.0f / s;  // correctly rounded
-    if (tmax.single_scale) {
+    if (TENSOR && tmax.single_scale) {
         if (blockIdx.x == 0 && threadIdx.x == 0) x_scale[0] = s;
     } else if (live && sub == 0 && slice == 0) {
         x_scale[row] = s;
@@ -486,8 +489,12 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
         return hipGetLastError();
     }
     const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
-    quant_rows_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
-        X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
+    if (tmax.partials)
+        quant_rows_kernel<XT, true><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+            X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
+    else
+        quant_rows_kernel<XT, false><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+            X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
     return hipGetLastError();
 }
 
