@@ -7,10 +7,11 @@
 // arithmetic and store phases of different blocks overlap.
 //
 // The quotient x / s is the correctly rounded IEEE one, computed without a division per
-// element: with r = 1 / s (one true division per row), q0 = x * r and two residual
-// corrections q <- fma(fma(-s, q, x), r, q) give RN(x / s) for every |x / s| that can round to
-// a non-zero code (Markstein's correction with a correctly rounded reciprocal; checked
-// against true division on the CPU over all bf16 inputs and random binary32 ones).
+// element: with r = RN(1 / s) (one true division per row) and q0 = RN(x * r), the residual
+// e = x - s * q0 is exact in one fma and q = RN(q0 + e * r) is RN(x / s) for every |x / s| that
+// can round to a non-zero code (Markstein's correction step: one suffices when the reciprocal
+// is correctly rounded; checked against true division on the CPU over all bf16 inputs, random
+// binary32 ones, constructed near-ties and the scales whose significand is all ones).
 #include "qc_internal.h"
 
 namespace qc {
@@ -69,12 +70,10 @@ __device__ inline int quant_code(float x, float s, float qmax) {
     return (int)r;
 }
 
-// RN(x / s) from r = RN(1 / s): product plus two fma residual corrections.
+// RN(x / s) from r = RN(1 / s): product, exact residual, one correction.
 __device__ inline float quotient(float x, float s, float r) {
-    float q = x * r;
-    q = fmaf(fmaf(-s, q, x), r, q);
-    q = fmaf(fmaf(-s, q, x), r, q);
-    return q;
+    const float q = x * r;
+    return fmaf(fmaf(-s, q, x), r, q);
 }
 
 // Four quotients -> four int8 codes in one dword.  Clamping to [-qmax, qmax] before rounding

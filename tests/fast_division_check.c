@@ -1,8 +1,9 @@
 /*
  * Host-side check of the division-free quotient the activation-quantization kernel uses:
- *     r = RN(1 / s);  q = x * r;  q = fma(fma(-s, q, x), r, q)  (twice)
- * against true IEEE binary32 division, over every bf16 input for many scales and over random
- * binary32 inputs including constructed near-ties.  The arithmetic is retyped here on purpose
+ *     r = RN(1 / s);  q = x * r;  q = fma(fma(-s, q, x), r, q)
+ * against true IEEE binary32 division, over every bf16 input for many scales, over random
+ * binary32 inputs including constructed near-ties, and (mode "edge") over the scales whose
+ * significand is all ones or nearly, where RN(1 / s) is least accurate.  The arithmetic is retyped here on purpose
  * (it shares no code with the GPU kernel): this validates the algorithm, the GPU parity
  * tests validate the implementation.  Prints "pairs quotient_mismatches_that_matter
  * code_mismatches"; quotient mismatches are only tolerated below 2^-30, where every code is 0.
@@ -15,7 +16,6 @@
 
 static float fast_quotient(float x, float s, float r) {
     float q = x * r;
-    q = fmaf(fmaf(-s, q, x), r, q);
     q = fmaf(fmaf(-s, q, x), r, q);
     return q;
 }
@@ -64,9 +64,38 @@ static int asym_main(long rows, long per_row, float levels) {
     return 0;
 }
 
+/* Scales with significand 0x7FFFF0 .. 0x7FFFFF over 140 exponents; x a (half-)integer or
+ * random multiple of s within +-255 steps, nudged by up to 3 ulps, half of them cut to bf16. */
+static int edge_main(long per_scale) {
+    long pairs = 0, bad_q = 0, bad_round = 0;
+    for (int e = 60; e < 200; ++e)
+        for (uint32_t m = 0x7FFFF0u; m <= 0x7FFFFFu; ++m) {
+            uint32_t sb = ((uint32_t)e << 23) | m, xb;
+            float s, x;
+            memcpy(&s, &sb, 4);
+            const float r = 1.0f / s;
+            for (long it = 0; it < per_scale; ++it) {
+                float k = (float)((int)(next() % 511) - 255) +
+                          ((it & 1) ? 0.5f : (float)(next() & 0xffff) / 65536.0f);
+                x = k * s;
+                memcpy(&xb, &x, 4);
+                xb += (uint32_t)(next() % 7) - 3;
+                if (it & 2) xb &= 0xffff0000u;
+                memcpy(&x, &xb, 4);
+                float q = x / s, f = fast_quotient(x, s, r);
+                ++pairs;
+                if (memcmp(&q, &f, 4) != 0 && fabsf(q) > 0x1p-30f) ++bad_q;
+                if (rintf(q) != rintf(f)) ++bad_round;
+            }
+        }
+    printf("%ld %ld %ld\n", pairs, bad_q, bad_round);
+    return 0;
+}
+
 int main(int argc, char **argv) {
     long scales = argc > 1 ? atol(argv[1]) : 400, randoms = argc > 2 ? atol(argv[2]) : 20000000;
     if (argc > 3) qmax = (float)atof(argv[3]);
+    if (argc > 4 && strcmp(argv[4], "edge") == 0) return edge_main(scales);
     if (argc > 4 && strcmp(argv[4], "asym") == 0) return asym_main(scales, randoms, qmax);
     long pairs = 0, bad_q = 0, bad_code = 0;
     for (long si = 0; si < scales; ++si) {
