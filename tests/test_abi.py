@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert qc.qc_version() == 1001
+    assert qc.qc_version() == 1002
     assert qc.status_string(0) == "QC_OK"
     for s in range(1, 5):
         assert qc.status_string(s).startswith("QC_ERR_")
