@@ -58,91 +58,183 @@ extern "C" float qc_prune_probability(float S, float tau_low, float tau_high, fl
     return p_base;
 }
 
+// ---- shared argument checks -------------------------------------------------------------------
+// Every entry point checks in the same order: INVALID_ARG (pointers, sizes, enums, alignment),
+// then UNSUPPORTED, then WORKSPACE; nothing is launched before all of them have passed.
+
+namespace {
+
+bool act_bits_ok(int b) { return b == 8 || b == 6 || b == 4; }
+
+// the activation side of a call: X [M, K] of xdt
+qc_status check_activation(const void *X, qc_dtype xdt, int64_t M, int64_t K) {
+    if (!X || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
+    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
+    if (!aligned(X, 16)) return QC_ERR_INVALID_ARG;
+    return QC_OK;
+}
+
+// the weight / output side of a linear: packed blob, scales, optional bias, Y [M, N]
+qc_status check_linear_side(const void *packed, const float *w_scale, const float *bias,
+                            qc_epilogue epi, const void *Y, qc_out ydt, int64_t M, int64_t K,
+                            int64_t N) {
+    if (!packed || !w_scale || !Y || M < 1 || K < 1 || N < 1) return QC_ERR_INVALID_ARG;
+    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
+    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) || (bias && !aligned(bias, 16)))
+        return QC_ERR_INVALID_ARG;
+    return QC_OK;
+}
+
+qc_status check_workspace_pointer(const void *workspace) {
+    return workspace && aligned(workspace, 256) ? QC_OK : QC_ERR_INVALID_ARG;
+}
+
+// what the quantization kernels take.  vector_only: the variant has no kernel for K that is not
+// a multiple of 16 or exceeds 9216; rot_block 0 = no rotation
+qc_status check_quant_supported(int64_t M, int64_t K, int act_bits, bool vector_only, int rot_block) {
+    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
+    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    if (vector_only && !quant_vector_path(K)) return QC_ERR_UNSUPPORTED;
+    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
+    return QC_OK;
+}
+
+// what the GEMM takes
+qc_status check_gemm_supported(int64_t M, int64_t K, int64_t N, int bits) {
+    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
+    const int64_t tiles = (round_up(M, kTileM) / kTileM) * (round_up(N, kTileN) / kTileN);
+    return tiles > 0x7fffffffLL ? QC_ERR_UNSUPPORTED : QC_OK;
+}
+
+#define QC_TRY(expr)                          \
+    do {                                      \
+        const qc_status st_ = (expr);         \
+        if (st_ != QC_OK) return st_;         \
+    } while (0)
+
+qc_status device_status(hipError_t e) { return e == hipSuccess ? QC_OK : QC_ERR_DEVICE; }
+
+// How the activations of a quantized linear are quantized.
+struct ActQuant {
+    int act_bits;
+    int rot_block;  // 0: no rotation
+};
+
+// stand-alone quantizer: codes row major
+qc_status quant_act_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, ActQuant how,
+                        int8_t *qx, float *x_scale, void *stream) {
+    QC_TRY(check_activation(X, xdt, M, K));
+    if (!qx || !x_scale || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
+    QC_TRY(check_quant_supported(M, K, how.act_bits, false, how.rot_block));
+    return device_status(launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, how.act_bits,
+                                          how.rot_block, (hipStream_t)stream));
+}
+
+// first half of a linear: codes in the GEMM's order + scales into the workspace
+qc_status qlinear_quant_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, ActQuant how,
+                            void *workspace, size_t workspace_bytes, void *stream) {
+    QC_TRY(check_activation(X, xdt, M, K));
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, how.act_bits, false, how.rot_block));
+    const ActWorkspace ws = act_workspace(M, K);
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    uint8_t *base = (uint8_t *)workspace;
+    return device_status(launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
+                                          (float *)base, how.act_bits, how.rot_block,
+                                          (hipStream_t)stream));
+}
+
+qc_status qlinear_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, ActQuant how,
+                      const void *packed, const float *w_scale, int bits, int64_t N,
+                      const float *bias, qc_epilogue epi, void *Y, qc_out ydt, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+    // both halves' checks up front, so that a failed call has no side effect
+    QC_TRY(check_activation(X, xdt, M, K));
+    QC_TRY(check_linear_side(packed, w_scale, bias, epi, Y, ydt, M, K, N));
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, how.act_bits, false, how.rot_block));
+    QC_TRY(check_gemm_supported(M, K, N, bits));
+    if (workspace_bytes < act_workspace(M, K).total_bytes) return QC_ERR_WORKSPACE;
+    QC_TRY(qlinear_quant_any(X, xdt, M, K, how, workspace, workspace_bytes, stream));
+    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
+                           ydt, stream);
+}
+
+}  // namespace
+
+// ---- per-token symmetric quantization (8, 6 or 4 bit codes), optionally rotated ------------------
+
 extern "C" size_t qc_qlinear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (M < 1 || K < 1 || N < 1 || K > QC_MAX_K) return 0;
     return act_workspace(M, K).total_bytes;
 }
 
-namespace {
-bool act_bits_ok(int b) { return b == 8 || b == 6 || b == 4; }
-}  // namespace
-
-namespace {
-// rot_block 0 = no rotation
-qc_status quant_act_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
-                        int rot_block, int8_t *qx, float *x_scale, void *stream) {
-    if (!X || !qx || !x_scale || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
-    hipError_t e = launch_quant_act(X, xdt, M, K, qx, nullptr, 0, x_scale, act_bits, rot_block,
-                                    (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
-}
-
-qc_status qlinear_quant_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
-                            int rot_block, void *workspace, size_t workspace_bytes, void *stream) {
-    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
-    const ActWorkspace ws = act_workspace(M, K);
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    uint8_t *base = (uint8_t *)workspace;
-    hipError_t e = launch_quant_act(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
-                                    (float *)base, act_bits, rot_block, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
-}
-
-qc_status qlinear_any(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
-                      int rot_block, const void *packed, const float *w_scale, int bits, int64_t N,
-                      const float *bias, qc_epilogue epi, void *Y, qc_out ydt, void *workspace,
-                      size_t workspace_bytes, void *stream) {
-    // every argument is checked before the first launch, so a failed call has no side effect
-    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
-        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
-    if (rot_block && !quant_rotation_supported(K, rot_block)) return QC_ERR_UNSUPPORTED;
-    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    const ActWorkspace ws = act_workspace(M, K);
-    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    qc_status st = qlinear_quant_any(X, xdt, M, K, act_bits, rot_block, workspace, workspace_bytes,
-                                     stream);
-    if (st != QC_OK) return st;
-    return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
-                           ydt, stream);
-}
-}  // namespace
-
 extern "C" qc_status qc_quant_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                        int act_bits, int8_t *qx, float *x_scale, void *stream) {
-    return quant_act_any(X, xdt, M, K, act_bits, 0, qx, x_scale, stream);
+    return quant_act_any(X, xdt, M, K, {act_bits, 0}, qx, x_scale, stream);
+}
+
+extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
+                                  float *x_scale, void *stream) {
+    return quant_act_any(X, xdt, M, K, {8, 0}, qx, x_scale, stream);
 }
 
 extern "C" qc_status qc_quant_act_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                       int act_bits, int rot_block, int8_t *qx, float *x_scale,
                                       void *stream) {
     if (rot_block == 0) return QC_ERR_UNSUPPORTED;
-    return quant_act_any(X, xdt, M, K, act_bits, rot_block, qx, x_scale, stream);
+    return quant_act_any(X, xdt, M, K, {act_bits, rot_block}, qx, x_scale, stream);
+}
+
+extern "C" qc_status qc_qlinear_quant_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                           int act_bits, void *workspace, size_t workspace_bytes,
+                                           void *stream) {
+    return qlinear_quant_any(X, xdt, M, K, {act_bits, 0}, workspace, workspace_bytes, stream);
+}
+
+extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                      void *workspace, size_t workspace_bytes, void *stream) {
+    return qlinear_quant_any(X, xdt, M, K, {8, 0}, workspace, workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_qlinear_quant_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                           int act_bits, int rot_block, void *workspace,
                                           size_t workspace_bytes, void *stream) {
     if (rot_block == 0) return QC_ERR_UNSUPPORTED;
-    return qlinear_quant_any(X, xdt, M, K, act_bits, rot_block, workspace, workspace_bytes, stream);
+    return qlinear_quant_any(X, xdt, M, K, {act_bits, rot_block}, workspace, workspace_bytes, stream);
+}
+
+extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
+                                     int64_t K, const void *packed, const float *w_scale, int bits,
+                                     int64_t N, const float *bias, qc_epilogue epi, void *Y,
+                                     qc_out ydt, void *stream) {
+    QC_TRY(check_linear_side(packed, w_scale, bias, epi, Y, ydt, M, K, N));
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_gemm_supported(M, K, N, bits));
+    const ActWorkspace ws = act_workspace(M, K);
+    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
+    const uint8_t *base = (const uint8_t *)workspace;
+    return device_status(launch_gemm(base + ws.scale_bytes, (const float *)base,
+                                     (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
+                                     ydt, nullptr, nullptr, (hipStream_t)stream));
+}
+
+extern "C" qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                         int act_bits, const void *packed, const float *w_scale,
+                                         int bits, int64_t N, const float *bias, qc_epilogue epi,
+                                         void *Y, qc_out ydt, void *workspace,
+                                         size_t workspace_bytes, void *stream) {
+    return qlinear_any(X, xdt, M, K, {act_bits, 0}, packed, w_scale, bits, N, bias, epi, Y, ydt,
+                       workspace, workspace_bytes, stream);
+}
+
+extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
+                                const void *packed, const float *w_scale, int bits, int64_t N,
+                                const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    return qlinear_any(X, xdt, M, K, {8, 0}, packed, w_scale, bits, N, bias, epi, Y, ydt, workspace,
+                       workspace_bytes, stream);
 }
 
 extern "C" qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int act_bits,
@@ -151,64 +243,8 @@ extern "C" qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int6
                                     qc_out ydt, void *workspace, size_t workspace_bytes,
                                     void *stream) {
     if (rot_block == 0) return QC_ERR_UNSUPPORTED;
-    return qlinear_any(X, xdt, M, K, act_bits, rot_block, packed, w_scale, bits, N, bias, epi, Y,
+    return qlinear_any(X, xdt, M, K, {act_bits, rot_block}, packed, w_scale, bits, N, bias, epi, Y,
                        ydt, workspace, workspace_bytes, stream);
-}
-
-extern "C" qc_status qc_quant_act(const void *X, qc_dtype xdt, int64_t M, int64_t K, int8_t *qx,
-                                  float *x_scale, void *stream) {
-    return qc_quant_act_bits(X, xdt, M, K, 8, qx, x_scale, stream);
-}
-
-extern "C" qc_status qc_qlinear_quant_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                           int act_bits, void *workspace, size_t workspace_bytes,
-                                           void *stream) {
-    return qlinear_quant_any(X, xdt, M, K, act_bits, 0, workspace, workspace_bytes, stream);
-}
-
-extern "C" qc_status qc_qlinear_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                      void *workspace, size_t workspace_bytes, void *stream) {
-    return qc_qlinear_quant_bits(X, xdt, M, K, 8, workspace, workspace_bytes, stream);
-}
-
-extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
-                                     int64_t K, const void *packed, const float *w_scale, int bits,
-                                     int64_t N, const float *bias, qc_epilogue epi, void *Y,
-                                     qc_out ydt, void *stream) {
-    if (!packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
-        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
-    const ActWorkspace ws = act_workspace(M, K);
-    const int64_t tiles = (ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN);
-    if (tiles > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    const uint8_t *base = (const uint8_t *)workspace;
-    hipError_t e = launch_gemm(base + ws.scale_bytes, (const float *)base, (const uint8_t *)packed,
-                               w_scale, bias, Y, M, N, K, bits, epi, ydt, nullptr, nullptr,
-                               (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
-}
-
-extern "C" qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                         int act_bits, const void *packed, const float *w_scale,
-                                         int bits, int64_t N, const float *bias, qc_epilogue epi,
-                                         void *Y, qc_out ydt, void *workspace,
-                                         size_t workspace_bytes, void *stream) {
-    return qlinear_any(X, xdt, M, K, act_bits, 0, packed, w_scale, bits, N, bias, epi, Y, ydt,
-                       workspace, workspace_bytes, stream);
-}
-
-extern "C" qc_status qc_qlinear(const void *X, qc_dtype xdt, int64_t M, int64_t K,
-                                const void *packed, const float *w_scale, int bits, int64_t N,
-                                const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
-                                void *workspace, size_t workspace_bytes, void *stream) {
-    return qc_qlinear_act_bits(X, xdt, M, K, 8, packed, w_scale, bits, N, bias, epi, Y, ydt,
-                               workspace, workspace_bytes, stream);
 }
 
 // ---- asymmetric activations (Section 3.1 Eq. (3)-(4) as printed) --------------------------------
@@ -221,32 +257,27 @@ extern "C" size_t qc_qlinear_asym_workspace_bytes(int64_t M, int64_t K, int64_t 
 extern "C" qc_status qc_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                        int act_bits, uint8_t *qx, float *x_scale, float *x_zero,
                                        void *stream) {
-    if (!X || !qx || !x_scale || !x_zero || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4) || !aligned(x_zero, 4))
+    QC_TRY(check_activation(X, xdt, M, K));
+    if (!qx || !x_scale || !x_zero || !aligned(qx, 16) || !aligned(x_scale, 4) || !aligned(x_zero, 4))
         return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (!quant_vector_path(K) || (M + 7) / 8 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    hipError_t e = launch_quant_act_asym(X, xdt, M, K, qx, nullptr, 0, x_scale, x_zero, act_bits,
-                                         false, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    QC_TRY(check_quant_supported(M, K, act_bits, true, 0));
+    return device_status(launch_quant_act_asym(X, xdt, M, K, qx, nullptr, 0, x_scale, x_zero,
+                                               act_bits, false, (hipStream_t)stream));
 }
 
 extern "C" qc_status qc_qlinear_asym_quant(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                            int act_bits, void *workspace, size_t workspace_bytes,
                                            void *stream) {
-    if (!X || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(workspace, 256)) return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (!quant_vector_path(K) || (M + 7) / 8 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    QC_TRY(check_activation(X, xdt, M, K));
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, act_bits, true, 0));
     const ActWorkspaceAsym ws = act_workspace_asym(M, K);
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
     uint8_t *base = (uint8_t *)workspace;
-    hipError_t e = launch_quant_act_asym(X, xdt, M, K, nullptr, base + ws.codes_offset, ws.sym.KF,
-                                         (float *)base, (float *)(base + ws.corr_offset), act_bits,
-                                         true, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    return device_status(launch_quant_act_asym(X, xdt, M, K, nullptr, base + ws.codes_offset,
+                                               ws.sym.KF, (float *)base,
+                                               (float *)(base + ws.corr_offset), act_bits, true,
+                                               (hipStream_t)stream));
 }
 
 extern "C" qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspace_bytes, int64_t M,
@@ -254,23 +285,18 @@ extern "C" qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspac
                                           const int32_t *w_row_sums, int bits, int64_t N,
                                           const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                                           void *stream) {
-    if (!packed || !w_scale || !w_row_sums || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(w_row_sums, 16) ||
-        !aligned(Y, 16) || !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (qc_packed_weight_bytes(N, K, bits) == 0 || !quant_vector_path(K)) return QC_ERR_UNSUPPORTED;
+    QC_TRY(check_linear_side(packed, w_scale, bias, epi, Y, ydt, M, K, N));
+    if (!w_row_sums || !aligned(w_row_sums, 16)) return QC_ERR_INVALID_ARG;
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_gemm_supported(M, K, N, bits));
+    if (!quant_vector_path(K)) return QC_ERR_UNSUPPORTED;
     const ActWorkspaceAsym ws = act_workspace_asym(M, K);
-    if ((ws.sym.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
     const uint8_t *base = (const uint8_t *)workspace;
-    hipError_t e = launch_gemm(base + ws.codes_offset, (const float *)base, (const uint8_t *)packed,
-                               w_scale, bias, Y, M, N, K, bits, epi, ydt,
-                               (const float *)(base + ws.corr_offset), w_row_sums,
-                               (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    return device_status(launch_gemm(base + ws.codes_offset, (const float *)base,
+                                     (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
+                                     ydt, (const float *)(base + ws.corr_offset), w_row_sums,
+                                     (hipStream_t)stream));
 }
 
 extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K,
@@ -278,24 +304,14 @@ extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int
                                      const int32_t *w_row_sums, int bits, int64_t N,
                                      const float *bias, qc_epilogue epi, void *Y, qc_out ydt,
                                      void *workspace, size_t workspace_bytes, void *stream) {
-    // every argument is checked before the first launch, so a failed call has no side effect
-    if (!X || !packed || !w_scale || !w_row_sums || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) ||
-        !aligned(w_row_sums, 16) || !aligned(Y, 16) || !aligned(workspace, 256) ||
-        (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (qc_packed_weight_bytes(N, K, bits) == 0 || !quant_vector_path(K)) return QC_ERR_UNSUPPORTED;
-    if ((M + 7) / 8 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    const ActWorkspaceAsym ws = act_workspace_asym(M, K);
-    if ((ws.sym.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
-    if (workspace_bytes < ws.total_bytes) return QC_ERR_WORKSPACE;
-    qc_status st = qc_qlinear_asym_quant(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream);
-    if (st != QC_OK) return st;
+    QC_TRY(check_activation(X, xdt, M, K));
+    QC_TRY(check_linear_side(packed, w_scale, bias, epi, Y, ydt, M, K, N));
+    if (!w_row_sums || !aligned(w_row_sums, 16)) return QC_ERR_INVALID_ARG;
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, act_bits, true, 0));
+    QC_TRY(check_gemm_supported(M, K, N, bits));
+    if (workspace_bytes < act_workspace_asym(M, K).total_bytes) return QC_ERR_WORKSPACE;
+    QC_TRY(qc_qlinear_asym_quant(X, xdt, M, K, act_bits, workspace, workspace_bytes, stream));
     return qc_qlinear_asym_gemm(workspace, workspace_bytes, M, K, packed, w_scale, w_row_sums, bits,
                                 N, bias, epi, Y, ydt, stream);
 }
@@ -310,16 +326,13 @@ extern "C" size_t qc_quant_act_tensor_workspace_bytes(int64_t M, int64_t K) {
 extern "C" qc_status qc_quant_act_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K,
                                          int act_bits, int8_t *qx, float *x_scale, void *workspace,
                                          size_t workspace_bytes, void *stream) {
-    if (!X || !qx || !x_scale || !workspace || M < 1 || K < 1) return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(qx, 16) || !aligned(x_scale, 4) || !aligned(workspace, 256))
-        return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (K > QC_MAX_K || (M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    QC_TRY(check_activation(X, xdt, M, K));
+    if (!qx || !x_scale || !aligned(qx, 16) || !aligned(x_scale, 4)) return QC_ERR_INVALID_ARG;
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, act_bits, false, 0));
     if (workspace_bytes < tensor_partials_bytes()) return QC_ERR_WORKSPACE;
-    hipError_t e = launch_quant_act_tensor(X, xdt, M, K, qx, nullptr, 0, x_scale, true,
-                                           (float *)workspace, act_bits, (hipStream_t)stream);
-    return e == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+    return device_status(launch_quant_act_tensor(X, xdt, M, K, qx, nullptr, 0, x_scale, true,
+                                                 (float *)workspace, act_bits, (hipStream_t)stream));
 }
 
 extern "C" size_t qc_qlinear_tensor_workspace_bytes(int64_t M, int64_t K, int64_t N) {
@@ -332,27 +345,20 @@ extern "C" qc_status qc_qlinear_tensor(const void *X, qc_dtype xdt, int64_t M, i
                                        int bits, int64_t N, const float *bias, qc_epilogue epi,
                                        void *Y, qc_out ydt, void *workspace, size_t workspace_bytes,
                                        void *stream) {
-    if (!X || !packed || !w_scale || !Y || !workspace || M < 1 || K < 1 || N < 1)
-        return QC_ERR_INVALID_ARG;
-    if (xdt != QC_F32 && xdt != QC_BF16) return QC_ERR_INVALID_ARG;
-    if (epi != QC_EPI_NONE && epi != QC_EPI_GELU_TANH && epi != QC_EPI_GELU_ERF) return QC_ERR_INVALID_ARG;
-    if (ydt != QC_OUT_F32 && ydt != QC_OUT_BF16 && ydt != QC_OUT_I32_ACC) return QC_ERR_INVALID_ARG;
-    if (!aligned(X, 16) || !aligned(packed, 256) || !aligned(w_scale, 16) || !aligned(Y, 16) ||
-        !aligned(workspace, 256) || (bias && !aligned(bias, 16)))
-        return QC_ERR_INVALID_ARG;
-    if (!act_bits_ok(act_bits)) return QC_ERR_UNSUPPORTED;
-    if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
-    if ((M + 3) / 4 > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
+    QC_TRY(check_activation(X, xdt, M, K));
+    QC_TRY(check_linear_side(packed, w_scale, bias, epi, Y, ydt, M, K, N));
+    QC_TRY(check_workspace_pointer(workspace));
+    QC_TRY(check_quant_supported(M, K, act_bits, false, 0));
+    QC_TRY(check_gemm_supported(M, K, N, bits));
     const ActWorkspace ws = act_workspace(M, K);
-    if ((ws.Mp / kTileM) * (round_up(N, kTileN) / kTileN) > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     if (workspace_bytes < ws.total_bytes + tensor_partials_bytes()) return QC_ERR_WORKSPACE;
     // [ the workspace of qc_qlinear ][ slab maxima ]: the first part is what qc_qlinear_gemm and
     // qc_debug_workspace_act read, with the one scale repeated for every token
     uint8_t *base = (uint8_t *)workspace;
-    hipError_t e = launch_quant_act_tensor(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
-                                           (float *)base, false, (float *)(base + ws.total_bytes),
-                                           act_bits, (hipStream_t)stream);
-    if (e != hipSuccess) return QC_ERR_DEVICE;
+    QC_TRY(device_status(launch_quant_act_tensor(X, xdt, M, K, nullptr, base + ws.scale_bytes, ws.KF,
+                                                 (float *)base, false,
+                                                 (float *)(base + ws.total_bytes), act_bits,
+                                                 (hipStream_t)stream)));
     return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
                            ydt, stream);
 }
