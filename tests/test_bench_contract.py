@@ -36,5 +36,8 @@ def test_one_json_line_with_the_contract_keys(extra):
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and 0.05 < rf["frac"] < 1.0
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
-    assert d["value"] > 100 * cb["value"]
+    assert d["value"] > 100 * cb["value"] and 0 < cb["one_thread"]["value"] <= cb["value"]
+    k = d["kernels"]
+    assert k["quant_act"]["cold"]["avg_launch_us"] > 0 and k["latent_delta"]["cold"]["avg_launch_us"] > 0
+    assert k["qlinear_whole_call"]["achieved"] < rf["achieved"]
     assert abs(d["value"] - 2.0 * 16384 * 3456 * 1152 / (d["ms_per_step"] * 1e-3) / 1e12) < 0.01 * d["value"]
