@@ -115,6 +115,56 @@ def cpu_baseline(case, act_bits=8, rot=0, asym=False, target_seconds=15.0):
             "seconds": dt}
 
 
+class PowerSampler:
+    """Reads the GPU's socket power and shader clock from sysfs every few milliseconds while
+    the timed loop runs (best effort: missing files give None)."""
+
+    def __init__(self):
+        import glob
+        import threading
+        self.power_file = (glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") + [None])[0]
+        self.cap_file = (glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap") + [None])[0]
+        self.clk_file = (glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk") + [None])[0]
+        self.power, self.clock = [], []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as f:
+                return f.read()
+        except (OSError, TypeError):
+            return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            p = self._read(self.power_file)
+            if p:
+                self.power.append(int(p) * 1e-6)
+            c = self._read(self.clk_file)
+            if c:
+                for line in c.splitlines():
+                    if "*" in line:
+                        self.clock.append(float(line.split(":")[1].lower().replace("mhz", "").replace("*", "")))
+            self._stop.wait(0.005)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join()
+
+    def summary(self):
+        cap = self._read(self.cap_file)
+        avg = lambda v: round(sum(v) / len(v), 1) if v else None
+        return {"power_cap_w": round(int(cap) * 1e-6, 1) if cap else None,
+                "power_w_avg": avg(self.power), "power_w_max": round(max(self.power), 1) if self.power else None,
+                "shader_clock_mhz_avg": avg(self.clock), "samples": len(self.power)}
+
+
 class Layer:
     """Device buffers of one quantized linear."""
 
@@ -286,11 +336,13 @@ def main():
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    with PowerSampler() as sampler:
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    device_info = dict(name=torch.cuda.get_device_name(0), **sampler.summary())
     ops = sum(L.ops for L in layers)
     value = ops / (ms_per_step * 1e-3) / 1e12
 
@@ -378,6 +430,7 @@ def main():
                    "offline_not_in_step": "qc_pack_weight",
                    "streams": "qc_qlinear on the current stream" +
                               ("" if sweep else ", qc_latent_delta on a second one")},
+        "device": device_info,
         "roofline": {"bound": "mfma", "kernel": kernel_name,
                      "achieved": round(gemm_tops, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
