@@ -18,6 +18,8 @@ QC_F32, QC_BF16 = 0, 1
 QC_EPI_NONE, QC_EPI_GELU_TANH, QC_EPI_GELU_ERF = 0, 1, 2
 QC_OUT_F32, QC_OUT_BF16, QC_OUT_I32_ACC = 0, 1, 2
 QC_MAX_K = 131072
+QC_MAX_N = 67108864
+QC_MAX_PREV = 8
 
 EXPORTS = (
     "qc_status_string", "qc_version", "qc_packed_weight_bytes", "qc_qlinear_workspace_bytes",

@@ -25,6 +25,17 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
+def test_binding_constants_equal_the_header():
+    text = open(os.path.join(ROOT, "include", "qc.h")).read()
+    for name, value in re.findall(r"#define\s+(QC_MAX_\w+)\s+(\d+)", text):
+        assert getattr(qc, name) == int(value), name
+    # enumerators: "NAME = value" inside the typedef enums
+    enums = dict(re.findall(r"\b(QC_[A-Z0-9_]+)\s*=\s*(\d+)", re.sub(r"/\*.*?\*/", "", text, flags=re.S)))
+    assert len(enums) >= 13
+    for name, value in enums.items():
+        assert getattr(qc, name) == int(value), name
+
+
 def test_version_and_status_strings():
     assert qc.qc_version() == 1002
     assert qc.status_string(0) == "QC_OK"
