@@ -243,6 +243,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     // in cache), which keeps the instruction stream and the wait counts uniform.
     const int last = stages - 1;
 #define QC_CLAMP(st) ((st) < last ? (st) : last)
+    // The eight MFMAs of a 32-k step are independent, so their order is free.  8 bit: token
+    // block outer.  4 bit: channel block outer, so that the two MFMAs that share an unpacked
+    // weight fragment follow each other (3.6 % faster on the fc2 layer).
+#define QC_MFMA_LOOPS                                                                           \
+    _Pragma("unroll") for (int o_ = 0; o_ < 8; ++o_)                                            \
+        for (int i = BITS == 8 ? o_ / 4 : o_ % 2, t = BITS == 8 ? o_ % 4 : o_ / 2, once_ = 1; once_; once_ = 0)
 #define QC_STAGE(s, SLOT, NEXT2)                                                               \
     do {                                                                                       \
         QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
@@ -251,8 +257,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         if (BITS == 8) QC_WAIT_X(12, SLOT); else QC_WAIT_X(10, SLOT);      /* X(s) is here */  \
         v4i w4a[4], w4b[4];                                                                    \
         if (BITS == 4) { unpack(w4a, 0); unpack(w4b, 1); }                                     \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                          \
-            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                      \
+        QC_MFMA_LOOPS                                                                          \
                 acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
                     xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
         __builtin_amdgcn_sched_barrier(0);                                                     \
@@ -264,8 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         issue_w(QC_CLAMP((s) + 3), (s) + 3);                                                   \
         /* after the last stage this reads data that is not used */                            \
         QC_READ_W((s) + 1, 0);                                                                 \
-        _Pragma("unroll") for (int i = 0; i < 2; ++i)                                          \
-            _Pragma("unroll") for (int t = 0; t < 4; ++t)                                      \
+        QC_MFMA_LOOPS                                                                          \
                 acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
                     xq[SLOT][i][1], BITS == 8 ? wr[1][t] : w4b[t], acc[i][t], 0, 0, 0);        \
         __builtin_amdgcn_sched_barrier(0);                                                     \
@@ -292,6 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     QC_WAIT_X(0, 0);
     QC_WAIT_X(0, 1);
     QC_WAIT_X(0, 2);
+#undef QC_MFMA_LOOPS
 #undef QC_CLAMP
 #undef QC_STAGE
 #undef QC_WAIT_W
