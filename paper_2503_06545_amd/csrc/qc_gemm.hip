@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         if (BITS == 8) QC_WAIT_W(4, 0); else QC_WAIT_W(0, 0);   /* k half 0 of W(s) is here */ \
         if (BITS == 8) QC_WAIT_X(12, SLOT); else QC_WAIT_X(10, SLOT);      /* X(s) is here */  \
         v4i w4a[4], w4b[4];                                                                    \
-        if (BITS == 4) { unpack(w4a, 0); unpack(w4b, 1); }                                     \
+        if (BITS == 4) unpack(w4a, 0);                                                         \
         QC_MFMA_LOOPS                                                                          \
                 acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
                     xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
@@ -266,6 +266,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         if (BITS == 8) QC_WAIT_W(0, 1);                                                        \
         __builtin_amdgcn_s_barrier(); /* ... and everybody else's: ring buffer s % 3 is free */\
         asm volatile("" ::: "memory");                                                         \
+        if (BITS == 4) unpack(w4b, 1);   /* before the reads below overwrite the nibbles */     \
         issue_w(QC_CLAMP((s) + 3), (s) + 3);                                                   \
         /* after the last stage this reads data that is not used */                            \
         QC_READ_W((s) + 1, 0);                                                                 \
