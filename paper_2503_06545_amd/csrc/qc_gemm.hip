@@ -237,8 +237,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     // loop is unrolled by three) so the activation ring stays in fixed registers.
     // VMEM operations complete in issue order; the issue order per wavefront is
     //   W(0) X(0) W(1) X(1) W(2), then in stage s: X(s+2), W(s+3)
-    // so behind X(s) come W(s+1) X(s+1) W(s+2) X(s+2) (2 FPW + 8 operations) and behind
-    // W(s+1) come X(s+1) W(s+2) X(s+2) (FPW + 8).  Past the end of K the stage index is
+    // X(s+2) goes out after the wait for X(s), among the first MFMAs of the stage, so at that
+    // wait W(s+1) X(s+1) W(s+2) are behind X(s) (2 FPW + 4 operations), and at the wait for
+    // W(s+1) in the middle of the stage X(s+1) W(s+2) X(s+2) are behind it (FPW + 8).  Past the end of K the stage index is
     // clamped to the last stage: those copies repeat data that is not used again (they hit
     // in cache), which keeps the instruction stream and the wait counts uniform.
     const int last = stages - 1;
@@ -251,12 +252,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         for (int i = BITS == 8 ? o_ / 4 : o_ % 2, t = BITS == 8 ? o_ % 4 : o_ / 2, once_ = 1; once_; once_ = 0)
 #define QC_STAGE(s, SLOT, NEXT2)                                                               \
     do {                                                                                       \
-        QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
         QC_READ_W((s), 1);                                                                     \
         if (BITS == 8) QC_WAIT_W(4, 0); else QC_WAIT_W(0, 0);   /* k half 0 of W(s) is here */ \
-        if (BITS == 8) QC_WAIT_X(12, SLOT); else QC_WAIT_X(10, SLOT);      /* X(s) is here */  \
+        if (BITS == 8) QC_WAIT_X(8, SLOT); else QC_WAIT_X(6, SLOT);        /* X(s) is here */  \
         v4i w4a[4], w4b[4];                                                                    \
         if (BITS == 4) unpack(w4a, 0);                                                         \
+        /* issued here, not before the waits, so that the loads go out under the MFMAs */      \
+        QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
         QC_MFMA_LOOPS                                                                          \
                 acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
                     xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
