@@ -252,13 +252,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         for (int i = BITS == 8 ? o_ / 4 : o_ % 2, t = BITS == 8 ? o_ % 4 : o_ / 2, once_ = 1; once_; once_ = 0)
 #define QC_STAGE(s, SLOT, NEXT2)                                                               \
     do {                                                                                       \
-        QC_READ_W((s), 1);                                                                     \
-        if (BITS == 8) QC_WAIT_W(4, 0); else QC_WAIT_W(0, 0);   /* k half 0 of W(s) is here */ \
+        QC_WAIT_W(0, 0);                                        /* k half 0 of W(s) is here */ \
         if (BITS == 8) QC_WAIT_X(8, SLOT); else QC_WAIT_X(6, SLOT);        /* X(s) is here */  \
         v4i w4a[4], w4b[4];                                                                    \
         if (BITS == 4) unpack(w4a, 0);                                                         \
         /* issued here, not before the waits, so that the loads go out under the MFMAs */      \
         QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
+        QC_READ_W((s), 1);                    /* k half 1: lands under the MFMAs of k half 0 */ \
         QC_MFMA_LOOPS                                                                          \
                 acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
                     xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
