@@ -1,22 +1,25 @@
 // Integer GEMM with fused dequantize / bias / GELU epilogue (Section 4.1 "Hardware
 // Implementation": the DiT linears as low-bit GEMMs with quantization fused around them).
 //
-//   acc[m, n] = sum_k qx[m, k] * qw[n, k]          exact, int32, v_mfma_i32_32x32x32_i8
+//   acc[m, n] = sum_k qx[m, k] * qw[n, k]          exact, int32, v_mfma_i32_16x16x64_i8
 //   Y[m, n]   = act(acc * sx[m] * sw[n] + bias[n])
 //
 // Block tile 256 tokens x 128 channels, 4 wavefronts stacked along the tokens, each
-// 64 x 128 = 2 x 4 MFMA tiles (128 accumulator registers), two blocks per CU so that one
+// 64 x 128 = 4 x 8 MFMA tiles (128 accumulator registers), two blocks per CU so that one
 // block's epilogue overlaps the other's MFMA loop.  Operands arrive pre-arranged as 1 KiB
 // MFMA fragments (see qc_internal.h).  The weight tile, which all four wavefronts use, goes
 // HBM -> LDS by linear direct-to-LDS copies through a 3-deep ring of 64-k stages and is read
 // back 16 B/lane, conflict free; the activation fragments are private to a wavefront and go
 // HBM -> registers directly (LDS writes are the scarce resource: about 64 B/clk/CU against
-// 256 B/clk/CU for reads).  Inside a stage the weight reads of the next 32 k are in flight
-// under the MFMAs of the current 32 k.  Tokens are the MFMA "A" operand (rows of the result
-// tile) and channels the "B" operand (columns = lanes); the weight row permutation makes a
-// lane's four tiles four consecutive channels, so half a wavefront stores 128 consecutive
-// channels of one token at a time.  The output is written with non-temporal stores: it is not
-// read again by this kernel and would otherwise push the operand panels out of the L2.
+// 256 B/clk/CU for reads).  Inside a stage the weight reads of the second half of the channels
+// are in flight under the MFMAs of the first half.  Tokens are the MFMA "A" operand (rows of the
+// result tile, four per lane) and channels the "B" operand (columns = lanes); the weight row
+// permutation makes a lane's eight tiles eight consecutive channels, so 16 lanes store 128
+// consecutive channels of one token at a time.  The 16x16x64 form of the MFMA is used because
+// the chip holds a higher clock on it than on the 32x32x32 form under its power cap (measured:
+// 4.1 against 3.4 POP/s on random operands, registers only).  The output is written with
+// non-temporal stores: it is not read again by this kernel and would otherwise push the operand
+// panels out of the L2.
 #include <type_traits>
 
 #include <atomic>
@@ -27,10 +30,10 @@ namespace qc {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
@@ -39,10 +42,10 @@ constexpr int kXSlots = 3;   // register ring of activation stages
 
 template <int BITS>
 struct StageLayout {
-    // Only the weight tile goes through LDS (all four wavefronts use all of it).  Fragments
-    // (1 KiB each) per 64-k stage: 8 bit 4 channel blocks x 2 k fragments; 4 bit one 64-k
-    // nibble unit per channel block.
-    static constexpr int kWFrags = BITS == 8 ? (kTileN / kFragRows) * 2 : (kTileN / kFragRows);
+    // Only the weight tile goes through LDS (all four wavefronts use all of it).  1 KiB pieces
+    // per 64-k stage: 8 bit one fragment per block of 16 channels; 4 bit one nibble unit per
+    // two such blocks.
+    static constexpr int kWFrags = BITS == 8 ? kTileN / kFragRows : kTileN / kFragRows / 2;
     static constexpr int kBytes = kWFrags * kFragBytes;
     static constexpr int kFragsPerWave = kWFrags / 4;
     static_assert(kWFrags % 4 == 0, "fragments must split evenly over 4 wavefronts");
@@ -58,7 +61,7 @@ struct GemmArgs {
     const float *bias;
     void *Y;
     int64_t M, N;
-    int KF;         // 32-k fragments per row (Kp / 32)
+    int KF;         // 64-k stages (Kp / 64)
     int m_tiles, n_tiles;
     int group_m;    // token tiles per patch of the block -> tile map
 };
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     int mt, nt;
     tile_of_block(blockIdx.x, gridDim.x, a.m_tiles, a.n_tiles, a.group_m, mt, nt);
 
-    const int stages = a.KF / 2;
+    const int stages = a.KF;
     // The epilogue's scales and bias are fetched now (one value per thread) and handed round
     // through LDS after the main loop, so that the epilogue does not start with a chain of L2
     // round trips.
@@ -144,88 +147,75 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
             }
         }
     }
-    // Weight fragments this wavefront copies HBM -> LDS, at stage 0.
-    const uint8_t *wsrc[FPW];
-#pragma unroll
-    for (int j = 0; j < FPW; ++j) {
-        const int f = wave * FPW + j;
-        if (BITS == 8) {
-            const int rb = f >> 1, kf = f & 1;
-            wsrc[j] = a.w_codes + ((int64_t)(nt * 4 + rb) * a.KF + kf) * kFragBytes + lane * 16;
-        } else {
-            wsrc[j] = a.w_codes + ((int64_t)(nt * 4 + f) * (a.KF / 2)) * kFragBytes + lane * 16;
-        }
-    }
-    constexpr int kWStep = BITS == 8 ? 2 * kFragBytes : kFragBytes;
-    // copy the weight fragments of K stage `stage` into ring buffer `ring % 3`
+    // The pieces of the weight stage tile this wavefront copies HBM -> LDS, at stage 0 (a
+    // stage tile is contiguous in memory).
+    const uint8_t *const wsrc = a.w_codes + (int64_t)nt * a.KF * L::kBytes + wave * FPW * kFragBytes + lane * 16;
+    // copy the weight pieces of K stage `stage` into ring buffer `ring % 3`
     auto issue_w = [&](int stage, int ring) {
         uint8_t *buf = lds + (ring % kStages) * L::kBytes;
 #pragma unroll
         for (int j = 0; j < FPW; ++j)
-            lds_dma_16(wsrc[j] + (int64_t)stage * kWStep, buf + (wave * FPW + j) * kFragBytes);
+            lds_dma_16(wsrc + (int64_t)stage * L::kBytes + j * kFragBytes, buf + (wave * FPW + j) * kFragBytes);
     };
 
     // Activation fragments are private to a wavefront (its 64 tokens), so they skip LDS:
-    // HBM -> registers, 16 B per lane, two stages ahead.  xq[slot][i][kf]: tokens 32 i ..,
-    // k half kf of the stage held in `slot`.  Loads and LDS reads are asm so that they stay
+    // HBM -> registers, 16 B per lane, two stages ahead.  xq[slot][i]: tokens 16 i .. of the
+    // stage held in `slot`.  Loads and LDS reads are asm so that they stay
     // in flight across loop iterations under explicit s_waitcnt counts; each wait names the
     // registers it makes valid, which orders the MFMAs that consume them behind it.
-    v4i xq[kXSlots][2][2];
-    const uint8_t *xsrc0 = a.x_tiled + ((int64_t)(mt * 8 + wave * 2 + 0) * a.KF) * kFragBytes + lane * 16;
-    const uint8_t *xsrc1 = a.x_tiled + ((int64_t)(mt * 8 + wave * 2 + 1) * a.KF) * kFragBytes + lane * 16;
+    v4i xq[kXSlots][4];
+    const uint8_t *const xsrc = a.x_tiled + ((int64_t)(mt * (kTileM / kWaveM) + wave) * a.KF) * (4 * kFragBytes) + lane * 16;
 
 #define QC_GLOBAL_LOAD(dst, ptr, imm) \
     asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(ptr), "n"(imm) : "memory")
 #define QC_ISSUE_X(stage, SLOT)                                              \
     do {                                                                     \
-        const uint8_t *p0_ = xsrc0 + (int64_t)(stage) * (2 * kFragBytes);    \
-        const uint8_t *p1_ = xsrc1 + (int64_t)(stage) * (2 * kFragBytes);    \
-        QC_GLOBAL_LOAD(xq[SLOT][0][0], p0_, 0);                              \
-        QC_GLOBAL_LOAD(xq[SLOT][0][1], p0_, kFragBytes);                     \
-        QC_GLOBAL_LOAD(xq[SLOT][1][0], p1_, 0);                              \
-        QC_GLOBAL_LOAD(xq[SLOT][1][1], p1_, kFragBytes);                     \
+        const uint8_t *p_ = xsrc + (int64_t)(stage) * (4 * kFragBytes);      \
+        QC_GLOBAL_LOAD(xq[SLOT][0], p_, 0);                                  \
+        QC_GLOBAL_LOAD(xq[SLOT][1], p_, kFragBytes);                         \
+        QC_GLOBAL_LOAD(xq[SLOT][2], p_, 2 * kFragBytes);                     \
+        QC_GLOBAL_LOAD(xq[SLOT][3], p_, 3 * kFragBytes);                     \
     } while (0)
 #define QC_WAIT_X(n, SLOT)                                                                    \
-    asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(xq[SLOT][0][0]), "+v"(xq[SLOT][0][1]),      \
-                 "+v"(xq[SLOT][1][0]), "+v"(xq[SLOT][1][1]))
+    asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(xq[SLOT][0]), "+v"(xq[SLOT][1]),            \
+                 "+v"(xq[SLOT][2]), "+v"(xq[SLOT][3]))
 
     // LDS -> registers for the weight fragments.
-    //   wr[kf][t]: t-th 32-channel block (8 bit);  wr[0][t]: its 64-k nibble unit (4 bit)
+    //   wr[h][t]: 16-channel block 4 h + t (8 bit);  wr[0][u]: nibble unit of blocks 2 u, 2 u + 1 (4 bit)
     v4i wr[2][4];
     const uint32_t lds_lane = (uint32_t)(uintptr_t)lds + lane * 16;  // LDS byte address of this lane
 #define QC_DS_READ(dst, addr, imm) \
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm))
-#define QC_READ_W(stage, KF)                                                         \
+#define QC_READ_W(stage, H)                                                          \
     do {                                                                             \
         const uint32_t base_ = lds_lane + ((stage) % kStages) * L::kBytes;           \
         if (BITS == 8) {                                                             \
-            QC_DS_READ(wr[KF][0], base_, (0 * 2 + KF) * kFragBytes);                 \
-            QC_DS_READ(wr[KF][1], base_, (1 * 2 + KF) * kFragBytes);                 \
-            QC_DS_READ(wr[KF][2], base_, (2 * 2 + KF) * kFragBytes);                 \
-            QC_DS_READ(wr[KF][3], base_, (3 * 2 + KF) * kFragBytes);                 \
-        } else if (KF == 0) {                                                        \
+            QC_DS_READ(wr[H][0], base_, (4 * H + 0) * kFragBytes);                   \
+            QC_DS_READ(wr[H][1], base_, (4 * H + 1) * kFragBytes);                   \
+            QC_DS_READ(wr[H][2], base_, (4 * H + 2) * kFragBytes);                   \
+            QC_DS_READ(wr[H][3], base_, (4 * H + 3) * kFragBytes);                   \
+        } else if (H == 0) {                                                        \
             QC_DS_READ(wr[0][0], base_, 0 * kFragBytes);                             \
             QC_DS_READ(wr[0][1], base_, 1 * kFragBytes);                             \
             QC_DS_READ(wr[0][2], base_, 2 * kFragBytes);                             \
             QC_DS_READ(wr[0][3], base_, 3 * kFragBytes);                             \
         }                                                                            \
     } while (0)
-#define QC_WAIT_W(n, KF) \
-    asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(wr[KF][0]), "+v"(wr[KF][1]), "+v"(wr[KF][2]), "+v"(wr[KF][3]))
+#define QC_WAIT_W(n, H) \
+    asm volatile("s_waitcnt lgkmcnt(" #n ")" : "+v"(wr[H][0]), "+v"(wr[H][1]), "+v"(wr[H][2]), "+v"(wr[H][3]))
 
-    v16i acc[2][4];
+    v4i acc[4][8];   // [16-token block][16-channel block]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
+        for (int t = 0; t < 8; ++t) acc[i][t] = v4i{0, 0, 0, 0};
 
-    // 4 bit: nibbles -> int8 operand dwords holding 16 * code
-    auto unpack = [&](v4i (&w)[4], int kf) {
+    // 4 bit: nibbles -> int8 operand dwords holding 16 * code, channel blocks 4 h .. 4 h + 3
+    auto unpack = [&](v4i (&w)[4], int h) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const uint32_t v0 = (uint32_t)wr[0][t][2 * kf], v1 = (uint32_t)wr[0][t][2 * kf + 1];
+            const v4i unit = wr[0][2 * h + t / 2];
+            const uint32_t v0 = (uint32_t)unit[2 * (t % 2)], v1 = (uint32_t)unit[2 * (t % 2) + 1];
             w[t][0] = (int)((v0 << 4) & 0xF0F0F0F0u);
             w[t][1] = (int)(v0 & 0xF0F0F0F0u);
             w[t][2] = (int)((v1 << 4) & 0xF0F0F0F0u);
@@ -244,24 +234,24 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     // in cache), which keeps the instruction stream and the wait counts uniform.
     const int last = stages - 1;
 #define QC_CLAMP(st) ((st) < last ? (st) : last)
-    // The eight MFMAs of a 32-k step are independent, so their order is free.  8 bit: token
-    // block outer.  4 bit: channel block outer, so that the two MFMAs that share an unpacked
-    // weight fragment follow each other (3.6 % faster on the fc2 layer).
+    // The sixteen MFMAs of a half stage (4 token blocks x 4 channel blocks) are independent, so
+    // their order is free.  8 bit: token block outer.  4 bit: channel block outer, so that the
+    // MFMAs that share an unpacked weight fragment follow each other.
 #define QC_MFMA_LOOPS                                                                           \
-    _Pragma("unroll") for (int o_ = 0; o_ < 8; ++o_)                                            \
-        for (int i = BITS == 8 ? o_ / 4 : o_ % 2, t = BITS == 8 ? o_ % 4 : o_ / 2, once_ = 1; once_; once_ = 0)
+    _Pragma("unroll") for (int o_ = 0; o_ < 16; ++o_)                                           \
+        for (int i = BITS == 8 ? o_ / 4 : o_ % 4, t = BITS == 8 ? o_ % 4 : o_ / 4, once_ = 1; once_; once_ = 0)
 #define QC_STAGE(s, SLOT, NEXT2)                                                               \
     do {                                                                                       \
-        QC_WAIT_W(0, 0);                                        /* k half 0 of W(s) is here */ \
+        QC_WAIT_W(0, 0);                                  /* channel half 0 of W(s) is here */ \
         if (BITS == 8) QC_WAIT_X(8, SLOT); else QC_WAIT_X(6, SLOT);        /* X(s) is here */  \
         v4i w4a[4], w4b[4];                                                                    \
         if (BITS == 4) unpack(w4a, 0);                                                         \
         /* issued here, not before the waits, so that the loads go out under the MFMAs */      \
         QC_ISSUE_X(QC_CLAMP((s) + 2), NEXT2);                                                  \
-        QC_READ_W((s), 1);                    /* k half 1: lands under the MFMAs of k half 0 */ \
+        QC_READ_W((s), 1);        /* channel half 1: lands under the MFMAs of channel half 0 */ \
         QC_MFMA_LOOPS                                                                          \
-                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
-                    xq[SLOT][i][0], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);        \
+                acc[i][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(                             \
+                    xq[SLOT][i], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);           \
         __builtin_amdgcn_sched_barrier(0);                                                     \
         QC_WAIT_VMCNT(FPW + 8);                                         /* W(s+1) has landed */\
         /* this wavefront's reads of W(s) are done ... */                                      \
@@ -273,8 +263,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         /* after the last stage this reads data that is not used */                            \
         QC_READ_W((s) + 1, 0);                                                                 \
         QC_MFMA_LOOPS                                                                          \
-                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                             \
-                    xq[SLOT][i][1], BITS == 8 ? wr[1][t] : w4b[t], acc[i][t], 0, 0, 0);        \
+                acc[i][4 + t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(                         \
+                    xq[SLOT][i], BITS == 8 ? wr[1][t] : w4b[t], acc[i][4 + t], 0, 0, 0);       \
         __builtin_amdgcn_sched_barrier(0);                                                     \
     } while (0)
 
@@ -322,104 +312,129 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     }
 
     // ---- epilogue: registers -> Y --------------------------------------------------------
-    // Lane (c = lane % 32, h = lane / 32) of MFMA tile (i, t) holds, in register r, token
-    // m0 + 32 i + 8 (r / 4) + 4 h + r % 4 and channel n0 + 4 c + t.
-    const int c = lane & 31, h = lane >> 5;
-    const int64_t n0 = (int64_t)nt * kTileN + 4 * c;
-    const int64_t m0 = (int64_t)mt * kTileM + wave * 64 + 4 * h;
+    // Lane (c = lane % 16, h = lane / 16) of MFMA tile (i, t) holds, in register r, token
+    // m0 + 16 i + 4 h + r and channel n0 + 8 c + t.
+    const int c = lane & 15, h = lane >> 4;
+    const int64_t n0 = (int64_t)nt * kTileN + 8 * c;
+    const int64_t m0 = (int64_t)mt * kTileM + wave * kWaveM + 4 * h;
+    constexpr int kOutBytes = OUT == QC_OUT_BF16 ? 2 : 4;
+    constexpr int kVecChannels = 16 / kOutBytes;  // channels in one 16 B store
     // A tile that lies wholly inside Y (the common case) takes a straight-line path with
-    // vector stores and no per-row tests; edge tiles test every row and channel.
+    // 16 B stores and no per-row tests; edge tiles test every row and channel.
     const bool interior = (int64_t)(mt + 1) * kTileM <= a.M && (int64_t)(nt + 1) * kTileN <= a.N &&
-                          (a.N % 4) == 0;  // uniform over the block
+                          (a.N % kVecChannels) == 0;  // uniform over the block
 
     // Row addresses: a block-uniform base (scalar registers) plus one 32-bit lane offset that is
     // the same for every row, so a row costs no vector address arithmetic.
-    constexpr int kOutBytes = OUT == QC_OUT_BF16 ? 2 : 4;
     char *const y_wave = reinterpret_cast<char *>(a.Y) +
-                         (((int64_t)mt * kTileM + wave * 64) * a.N + (int64_t)nt * kTileN) * kOutBytes;
-    const uint32_t lane_off = (uint32_t)((4 * h * a.N + 4 * c) * kOutBytes);  // N <= 2^26
+                         (((int64_t)mt * kTileM + wave * kWaveM) * a.N + (int64_t)nt * kTileN) * kOutBytes;
+    const uint32_t lane_off = (uint32_t)((4 * h * a.N + 8 * c) * kOutBytes);  // N <= 2^26
 
     auto write_tile = [&](auto checked_tag) {
         constexpr bool CHECKED = decltype(checked_tag)::value;
         if (CHECKED && n0 >= a.N) return;
-        const bool full = !CHECKED || ((a.N % 4) == 0 && n0 + 4 <= a.N);
+        // which of the lane's two groups of four channels may be written as a vector, and
+        // whether all eight may go out as one 16 B store (bf16)
+        bool vec[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) vec[j] = !CHECKED || ((a.N % 4) == 0 && n0 + 4 * j + 4 <= a.N);
+        const bool vec8 = !CHECKED || (vec[1] && (a.N % 8) == 0);
 
-        float sw[4] = {0.f, 0.f, 0.f, 0.f}, bs[4] = {0.f, 0.f, 0.f, 0.f}, rs[4] = {0.f, 0.f, 0.f, 0.f};
+        float sw[8], bs[8], rs[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) sw[t] = bs[t] = rs[t] = 0.0f;
         if (OUT != QC_OUT_I32_ACC) {
-            const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 4 * c);
-            const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 4 * c);
-            sw[0] = s4.x; sw[1] = s4.y; sw[2] = s4.z; sw[3] = s4.w;
-            bs[0] = b4.x; bs[1] = b4.y; bs[2] = b4.z; bs[3] = b4.w;
-            if (ASYM) {
-                const float4 r4 = *reinterpret_cast<const float4 *>(lds_rs + 4 * c);
-                rs[0] = r4.x; rs[1] = r4.y; rs[2] = r4.z; rs[3] = r4.w;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float4 s4 = *reinterpret_cast<const float4 *>(lds_sw + 8 * c + 4 * j);
+                const float4 b4 = *reinterpret_cast<const float4 *>(lds_bs + 8 * c + 4 * j);
+                sw[4 * j + 0] = s4.x; sw[4 * j + 1] = s4.y; sw[4 * j + 2] = s4.z; sw[4 * j + 3] = s4.w;
+                bs[4 * j + 0] = b4.x; bs[4 * j + 1] = b4.y; bs[4 * j + 2] = b4.z; bs[4 * j + 3] = b4.w;
+                if (ASYM) {
+                    const float4 r4 = *reinterpret_cast<const float4 *>(lds_rs + 8 * c + 4 * j);
+                    rs[4 * j + 0] = r4.x; rs[4 * j + 1] = r4.y; rs[4 * j + 2] = r4.z; rs[4 * j + 3] = r4.w;
+                }
             }
         }
 
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int64_t m4 = m0 + 32 * i + 8 * g;
-                if (CHECKED && m4 >= a.M) continue;
-                float sx[4] = {0.f, 0.f, 0.f, 0.f}, cx[4] = {0.f, 0.f, 0.f, 0.f};
-                if (OUT != QC_OUT_I32_ACC) {
-                    const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * 64 + 4 * h + 32 * i + 8 * g);
-                    sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
-                    if (ASYM) {
-                        const float4 c4 = *reinterpret_cast<const float4 *>(lds_cx + wave * 64 + 4 * h + 32 * i + 8 * g);
-                        cx[0] = c4.x; cx[1] = c4.y; cx[2] = c4.z; cx[3] = c4.w;
-                    }
+        for (int i = 0; i < 4; ++i) {
+            const int64_t m4 = m0 + 16 * i;
+            if (CHECKED && m4 >= a.M) continue;
+            float sx[4] = {0.f, 0.f, 0.f, 0.f}, cx[4] = {0.f, 0.f, 0.f, 0.f};
+            if (OUT != QC_OUT_I32_ACC) {
+                const float4 x4 = *reinterpret_cast<const float4 *>(lds_sx + wave * kWaveM + 16 * i + 4 * h);
+                sx[0] = x4.x; sx[1] = x4.y; sx[2] = x4.z; sx[3] = x4.w;
+                if (ASYM) {
+                    const float4 c4 = *reinterpret_cast<const float4 *>(lds_cx + wave * kWaveM + 16 * i + 4 * h);
+                    cx[0] = c4.x; cx[1] = c4.y; cx[2] = c4.z; cx[3] = c4.w;
                 }
+            }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t m = m4 + q;
-                    if (CHECKED && m >= a.M) continue;
-                    int raw[4];
+            for (int q = 0; q < 4; ++q) {
+                if (CHECKED && m4 + q >= a.M) continue;
+                int raw[8];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) raw[t] = acc[i][t][4 * g + q];
-                    char *const y_row = y_wave + (int64_t)(32 * i + 8 * g + q) * a.N * kOutBytes + lane_off;
-                    if (OUT == QC_OUT_I32_ACC) {
-                        int32_t *y = reinterpret_cast<int32_t *>(y_row);
-                        if (BITS == 4) {
+                for (int t = 0; t < 8; ++t) raw[t] = acc[i][t][q];
+                char *const y_row = y_wave + (int64_t)(16 * i + q) * a.N * kOutBytes + lane_off;
+                if (OUT == QC_OUT_I32_ACC) {
+                    int32_t *y = reinterpret_cast<int32_t *>(y_row);
+                    if (BITS == 4) {
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) raw[t] >>= 4;  // exact: multiples of 16
-                        }
-                        if (full) {
-                            __builtin_nontemporal_store(v4i{raw[0], raw[1], raw[2], raw[3]}, reinterpret_cast<v4i *>(y));
+                        for (int t = 0; t < 8; ++t) raw[t] >>= 4;  // exact: multiples of 16
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        if (vec[j]) {
+                            __builtin_nontemporal_store(v4i{raw[4 * j], raw[4 * j + 1], raw[4 * j + 2], raw[4 * j + 3]},
+                                                        reinterpret_cast<v4i *>(y + 4 * j));
                         } else {
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
+                            for (int t = 4 * j; t < 4 * j + 4; ++t) if (n0 + t < a.N) y[t] = raw[t];
+                        }
+                    }
+                } else {
+                    float v[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        float af = (float)raw[t];
+                        if (ASYM) af = fmaf(cx[q], rs[t], af);
+                        float y = fmaf(af * sx[q], sw[t], bs[t]);
+                        if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
+                        else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
+                        v[t] = y;
+                    }
+                    if (OUT == QC_OUT_F32) {
+                        float *y = reinterpret_cast<float *>(y_row);
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            if (vec[j]) {
+                                __builtin_nontemporal_store(f4{v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]},
+                                                            reinterpret_cast<f4 *>(y + 4 * j));
+                            } else {
+#pragma unroll
+                                for (int t = 4 * j; t < 4 * j + 4; ++t) if (n0 + t < a.N) y[t] = v[t];
+                            }
                         }
                     } else {
-                        float v[4];
+                        uint16_t *y = reinterpret_cast<uint16_t *>(y_row);
+                        uint32_t pk[4];
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            float af = (float)raw[t];
-                            if (ASYM) af = fmaf(cx[q], rs[t], af);
-                            float y = fmaf(af * sx[q], sw[t], bs[t]);
-                            if (EPI == QC_EPI_GELU_TANH) y = gelu_tanh_f(y);
-                            else if (EPI == QC_EPI_GELU_ERF) y = gelu_erf_f(y);
-                            v[t] = y;
-                        }
-                        if (OUT == QC_OUT_F32) {
-                            float *y = reinterpret_cast<float *>(y_row);
-                            if (full) {
-                                __builtin_nontemporal_store(f4{v[0], v[1], v[2], v[3]}, reinterpret_cast<f4 *>(y));
-                            } else {
-#pragma unroll
-                                for (int t = 0; t < 4; ++t) if (n0 + t < a.N) y[t] = v[t];
-                            }
+                        for (int j = 0; j < 4; ++j) pk[j] = pack_bf16x2(v[2 * j], v[2 * j + 1]);
+                        if (vec8) {
+                            __builtin_nontemporal_store(u4{pk[0], pk[1], pk[2], pk[3]}, reinterpret_cast<u4 *>(y));
                         } else {
-                            uint16_t *y = reinterpret_cast<uint16_t *>(y_row);
-                            const uint32_t lo = pack_bf16x2(v[0], v[1]), hi = pack_bf16x2(v[2], v[3]);
-                            if (full) {
-                                __builtin_nontemporal_store(u2{lo, hi}, reinterpret_cast<u2 *>(y));
-                            } else {
-                                if (n0 + 0 < a.N) y[0] = (uint16_t)(lo & 0xffffu);
-                                if (n0 + 1 < a.N) y[1] = (uint16_t)(lo >> 16);
-                                if (n0 + 2 < a.N) y[2] = (uint16_t)(hi & 0xffffu);
-                                if (n0 + 3 < a.N) y[3] = (uint16_t)(hi >> 16);
+#pragma unroll
+                            for (int j = 0; j < 2; ++j) {
+                                if (vec[j]) {
+                                    __builtin_nontemporal_store(u2{pk[2 * j], pk[2 * j + 1]},
+                                                                reinterpret_cast<u2 *>(y + 4 * j));
+                                } else {
+#pragma unroll
+                                    for (int t = 4 * j; t < 4 * j + 4; ++t)
+                                        if (n0 + t < a.N)
+                                            y[t] = (uint16_t)(t % 2 ? pk[t / 2] >> 16 : pk[t / 2] & 0xffffu);
+                                }
                             }
                         }
                     }

@@ -11,43 +11,67 @@ namespace qc {
 // ---- data layout of the GEMM operands in HBM -------------------------------------------
 //
 // Both GEMM operands are stored as "fragments": the 1 KiB a 64-lane wavefront hands to one
-// v_mfma_i32_32x32x32_i8 as its A or B operand, lane after lane (lane l supplies 16
-// consecutive k of row l % 32, k half l / 32).  A fragment therefore covers 32 rows x 32 k,
-// and a wavefront moves it HBM -> LDS -> registers with fully linear 16 B/lane accesses.
+// v_mfma_i32_16x16x64_i8 as its A or B operand, lane after lane (lane l supplies the 16
+// consecutive k of row l % 16 that start at 16 (l / 16)).  A fragment therefore covers
+// 16 rows x 64 k, and a wavefront moves it HBM -> LDS -> registers with fully linear 16 B/lane
+// accesses.  (The 16x16x64 form of the instruction is used because under the power cap it runs
+// at a higher clock than the 32x32x32 form: it reads more operand but less accumulator data
+// per multiply.)  With KF = Kp / 64 and Kp = K rounded up to 192:
 //
-//   fragment index   = (row / 32) * KF + k / 32          KF = Kp / 32, Kp = K rounded up to 192
-//   byte in fragment = (((k % 32) / 16) * 32 + row % 32) * 16 + k % 16
+//   activations, token m:  fragment ((m / 64) * KF + k / 64) * 4 + (m % 64) / 16, row m % 16
+//       (the 4 KiB a wavefront of the GEMM needs per 64-k stage are contiguous)
+//   weights, channel n = 128 G + 8 c + t:  fragment (G * KF + k / 64) * 8 + t, row c
+//       (the 8 KiB stage tile of a block is contiguous; a lane of the GEMM ends up holding 8
+//       consecutive output channels of one token, i.e. one 16 B bf16 store, 16 lanes covering
+//       128 consecutive channels)
+//   byte in fragment = (((k % 64) / 16) * 16 + row) * 16 + k % 16
 //
-// Activations use their token index as `row`.  Weights use a permuted row index p so that a
-// lane of the GEMM ends up holding 4 consecutive output channels of one token (one 8 B bf16
-// or 16 B float store, 32 lanes covering 128 consecutive channels): inside each group of
-// 128 channels, channel n = 128 G + r sits at p = 128 G + 32 * (r % 4) + r / 4.
-// 4-bit weights keep the same (p, k) -> lane mapping but one 1 KiB unit spans 64 k: lane l
-// holds 8 bytes of nibbles for the even 32-k fragment and 8 bytes for the odd one.  Inside a
-// dword of 8 nibbles, k offset e (0..7) sits in nibble (e < 4 ? 2 e : 2 (e - 4) + 1), so that
-// (v << 4) & 0xF0F0F0F0 and v & 0xF0F0F0F0 are the int8 operand dwords (codes times 16).
+// 4-bit weights keep the same (n, k) -> lane mapping but one 1 KiB unit holds two fragments'
+// worth of nibbles: unit (G * KF + k / 64) * 4 + t / 2, where lane l has 8 bytes for fragment
+// t even followed by 8 bytes for t odd.  Inside a dword of 8 nibbles, k offset e (0..7) sits in
+// nibble (e < 4 ? 2 e : 2 (e - 4) + 1), so that (v << 4) & 0xF0F0F0F0 and v & 0xF0F0F0F0 are
+// the int8 operand dwords (codes times 16).
 
-constexpr int kFragRows = 32;
-constexpr int kFragK = 32;
+constexpr int kFragRows = 16;
+constexpr int kFragK = 64;
 constexpr int kFragBytes = 1024;
 constexpr int kKAlign = 192;       // K is padded to this: three 64-k pipeline stages of the GEMM
 constexpr int kTileM = 256;        // GEMM block tile, tokens
 constexpr int kTileN = 128;        // GEMM block tile, output channels
+constexpr int kWaveM = 64;         // tokens of one wavefront of the GEMM
 constexpr int kPackedHeaderBytes = 256;
-constexpr uint32_t kPackedTag = 0x51433031u;  // "QC01"
+constexpr uint32_t kPackedTag = 0x51433032u;  // "QC02"
 constexpr float kAbsmaxFloor = 0x1p-64f;
 
 __host__ __device__ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-__host__ __device__ inline int64_t frag_offset(int64_t row, int64_t k, int64_t KF) {
-    return ((row / kFragRows) * KF + k / kFragK) * kFragBytes +
-           (((k % kFragK) / 16) * 32 + row % kFragRows) * 16 + k % 16;
+__host__ __device__ inline int64_t byte_in_frag(int64_t row16, int64_t k) {
+    return (((k % kFragK) / 16) * 16 + row16) * 16 + k % 16;
 }
 
-__host__ __device__ inline int64_t weight_row_of_channel(int64_t n) {
-    const int64_t r = n % 128;
-    return (n - r) + 32 * (r % 4) + r / 4;
+// byte offset of activation code (m, k) from the start of the tiled codes
+__host__ __device__ inline int64_t act_frag_offset(int64_t m, int64_t k, int64_t KF) {
+    const int64_t frag = ((m / kWaveM) * KF + k / kFragK) * (kWaveM / kFragRows) + (m % kWaveM) / kFragRows;
+    return frag * kFragBytes + byte_in_frag(m % kFragRows, k);
 }
+
+// byte offset of 8-bit weight code (n, k) from the start of the code area
+__host__ __device__ inline int64_t weight_frag_offset(int64_t n, int64_t k, int64_t KF) {
+    const int64_t r = n % kTileN;
+    const int64_t frag = ((n / kTileN) * KF + k / kFragK) * (kTileN / kFragRows) + r % 8;
+    return frag * kFragBytes + byte_in_frag(r / 8, k);
+}
+
+// byte offset (from the start of the code area) of the dword that holds the 8 nibbles of
+// channel n, k = k8 .. k8 + 7 (k8 a multiple of 8)
+__host__ __device__ inline int64_t w4_dword_offset(int64_t n, int64_t k8, int64_t KF) {
+    const int64_t r = n % kTileN, t = r % 8;
+    const int64_t unit = ((n / kTileN) * KF + k8 / kFragK) * (kTileN / kFragRows / 2) + t / 2;
+    const int64_t lane = ((k8 % kFragK) / 16) * 16 + r / 8;
+    return unit * kFragBytes + lane * 16 + (t % 2) * 8 + ((k8 % 16) / 8) * 4;
+}
+
+__host__ __device__ inline int w4_nibble_of(int e) { return e < 4 ? 2 * e : 2 * (e - 4) + 1; }
 
 // workspace of qc_qlinear: [ x_scale: Mp floats ][ tiled codes: Mp * Kp bytes ]
 struct ActWorkspace {

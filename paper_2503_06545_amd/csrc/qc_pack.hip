@@ -14,16 +14,6 @@ __device__ inline int weight_code(float w, float s, float qmax) {
     return (int)r;
 }
 
-// byte offset (from the start of the code area) of the dword that holds the 8 nibbles of
-// packed row p, k = k8 .. k8 + 7 (k8 a multiple of 8)
-__device__ __host__ inline int64_t w4_dword_offset(int64_t p, int64_t k8, int64_t KF) {
-    const int64_t lane = ((k8 % 32) / 16) * 32 + p % 32;
-    return ((p / 32) * (KF / 2) + k8 / 64) * kFragBytes + lane * 16 + ((k8 % 64) / 32) * 8 +
-           ((k8 % 16) / 8) * 4;
-}
-
-__device__ __host__ inline int w4_nibble_of(int e) { return e < 4 ? 2 * e : 2 * (e - 4) + 1; }
-
 // Eight consecutive weights of a row, k = k8 .. k8 + 7 (zeros past K or for a padding row),
 // after the counter-rotation that matches rotated activations (Section 3.2 AIGQ (1), Section
 // 4.1): each block of `rot` columns times the Walsh-Hadamard matrix, then times 1 / rot.  Same
@@ -93,7 +83,6 @@ __global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__re
 
     uint8_t *codes = blob + kPackedHeaderBytes;
     const int64_t KF = Kp / kFragK;
-    const int64_t p = weight_row_of_channel(n);
     for (int64_t t = 0; t < trips; ++t) {
         const int64_t k8 = (t * 64 + lane) * 8;
         float v[8];
@@ -107,12 +96,12 @@ __global__ __launch_bounds__(kThreads) void pack_weight_kernel(const float *__re
             uint2 out;
             out.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | ((uint32_t)(c[3] & 0xff) << 24);
             out.y = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | ((uint32_t)(c[7] & 0xff) << 24);
-            *reinterpret_cast<uint2 *>(codes + frag_offset(p, k8, KF)) = out;
+            *reinterpret_cast<uint2 *>(codes + weight_frag_offset(n, k8, KF)) = out;
         } else {
             uint32_t out = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) out |= (uint32_t)(c[e] & 0xf) << (4 * w4_nibble_of(e));
-            *reinterpret_cast<uint32_t *>(codes + w4_dword_offset(p, k8, KF)) = out;
+            *reinterpret_cast<uint32_t *>(codes + w4_dword_offset(n, k8, KF)) = out;
         }
     }
 }
@@ -126,12 +115,11 @@ __global__ __launch_bounds__(kThreads) void unpack_weight_kernel(const uint8_t *
     const int64_t n = idx / K, k = idx % K;
     const uint8_t *codes = blob + kPackedHeaderBytes;
     const int64_t KF = Kp / kFragK;
-    const int64_t p = weight_row_of_channel(n);
     if (bits == 8) {
-        out[idx] = (int8_t)codes[frag_offset(p, k, KF)];
+        out[idx] = (int8_t)codes[weight_frag_offset(n, k, KF)];
     } else {
         const int64_t k8 = k - k % 8;
-        const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(p, k8, KF));
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(n, k8, KF));
         const int nib = (int)((v >> (4 * w4_nibble_of((int)(k % 8)))) & 0xf);
         out[idx] = (int8_t)(nib >= 8 ? nib - 16 : nib);
     }
@@ -149,18 +137,17 @@ __global__ __launch_bounds__(kThreads) void weight_row_sums_kernel(const uint8_t
     if (n >= N) return;
     const uint8_t *codes = blob + kPackedHeaderBytes;
     const int64_t KF = Kp / kFragK;
-    const int64_t p = weight_row_of_channel(n);
     int32_t acc = 0;
     for (int64_t k8 = (int64_t)lane * 8; k8 < K; k8 += 64 * 8) {
         if (bits == 8) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(codes + frag_offset(p, k8, KF));
+            const uint2 v = *reinterpret_cast<const uint2 *>(codes + weight_frag_offset(n, k8, KF));
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t w = e < 4 ? v.x : v.y;
                 if (k8 + e < K) acc += (int32_t)(int8_t)((w >> (8 * (e & 3))) & 0xff);
             }
         } else {
-            const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(p, k8, KF));
+            const uint32_t v = *reinterpret_cast<const uint32_t *>(codes + w4_dword_offset(n, k8, KF));
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int nib = (int)((v >> (4 * w4_nibble_of(e))) & 0xf);
@@ -189,7 +176,7 @@ __global__ __launch_bounds__(kThreads) void untile_act_asym_kernel(const uint8_t
     }
     if (idx >= M * K) return;
     const int64_t m = idx / K, k = idx % K;
-    qx[idx] = (uint8_t)((int)(int8_t)tiled[frag_offset(m, k, KF)] + shift);
+    qx[idx] = (uint8_t)((int)(int8_t)tiled[act_frag_offset(m, k, KF)] + shift);
 }
 
 __global__ __launch_bounds__(kThreads) void untile_act_kernel(const uint8_t *__restrict__ tiled,
@@ -201,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void untile_act_kernel(const uint8_t *__r
     if (idx < M) x_scale[idx] = scales[idx];
     if (idx >= M * K) return;
     const int64_t m = idx / K, k = idx % K;
-    qx[idx] = (int8_t)tiled[frag_offset(m, k, KF)];
+    qx[idx] = (int8_t)tiled[act_frag_offset(m, k, KF)];
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }

@@ -211,8 +211,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     if (!live) return;
 
     int8_t *out_rows = qx ? qx + row * K : nullptr;
-    uint8_t *out_tiled = qx_tiled ? qx_tiled + (row / kFragRows) * KF * kFragBytes + (row % kFragRows) * 16
-                                  : nullptr;
+    uint8_t *out_tiled = qx_tiled ? qx_tiled + act_frag_offset(row, 0, KF) : nullptr;
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
@@ -224,9 +223,9 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
                           quotient(u[i].get(4 * d + 2), s, r), quotient(u[i].get(4 * d + 3), s, r), qmax);
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
         if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
-        // unit ui covers k = 16 ui ..: fragment ui / 2, k half ui % 2 (see frag_offset)
+        // unit ui covers k = 16 ui ..: 64-k stage ui / 4, k quarter ui % 4 (see act_frag_offset)
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 1) * kFragBytes + (ui & 1) * 512) = out;
+            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
     }
 }
 
@@ -321,8 +320,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
     if (!live) return;
 
     int8_t *out_rows = qx ? qx + row * K : nullptr;
-    uint8_t *out_tiled = qx_tiled ? qx_tiled + (row / kFragRows) * KF * kFragBytes + (row % kFragRows) * 16
-                                  : nullptr;
+    uint8_t *out_tiled = qx_tiled ? qx_tiled + act_frag_offset(row, 0, KF) : nullptr;
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
@@ -335,7 +333,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
         if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 1) * kFragBytes + (ui & 1) * 512) = out;
+            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
     }
 }
 
@@ -407,8 +405,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
     const float magic = 12582912.0f;  // 1.5 * 2^23: the sum's low byte is the integer's low byte
 
     uint8_t *out_rows = qx ? qx + row * K : nullptr;
-    uint8_t *out_tiled = qx_tiled ? qx_tiled + (row / kFragRows) * KF * kFragBytes + (row % kFragRows) * 16
-                                  : nullptr;
+    uint8_t *out_tiled = qx_tiled ? qx_tiled + act_frag_offset(row, 0, KF) : nullptr;
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
@@ -427,7 +424,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
         if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 1) * kFragBytes + (ui & 1) * 512) = out;
+            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
     }
 }
 
@@ -463,7 +460,7 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
     for (int64_t k = lane; k < K; k += 64) {
         const int8_t c = (int8_t)quant_code(widen(xrow[k]), s, qmax);
         if (qx) qx[row * K + k] = c;
-        if (qx_tiled) qx_tiled[frag_offset(row, k, KF)] = (uint8_t)c;
+        if (qx_tiled) qx_tiled[act_frag_offset(row, k, KF)] = (uint8_t)c;
     }
 }
 

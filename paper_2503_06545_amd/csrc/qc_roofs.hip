@@ -108,6 +108,35 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
     if (s == 0x7fffffff) out[0] = s;
 }
 
+// The same amount of work per iteration with the 16x16x64 form of the instruction (32 MFMAs on a
+// 64x128 accumulator patch): twice the operand reads and the same accumulator traffic per MAC.
+__global__ __launch_bounds__(256, 2) void mfma16_kernel(const v4i *__restrict__ data, int iters,
+                                                        int *out) {
+    v4i acc[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[i][t] = v4i{0, 0, 0, 0};
+    v4i a[4], b[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = data[(threadIdx.x * 4 + i) & 1023];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = data[(threadIdx.x * 8 + i + 512) & 1023];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                acc[i][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[t], acc[i][t], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) s += acc[i][t][0] + acc[i][t][3];
+    if (s == 0x7fffffff) out[0] = s;
+}
+
 // ---- LDS -------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void lds_read_kernel(int iters, int *out) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[16384];
@@ -245,6 +274,10 @@ int main() {
            tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_zero, gsrc, iters, dout); })));
     printf("mfma same, random int8 operands:                                               %5.0f TOPS\n",
            tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    printf("mfma v_mfma_i32_16x16x64_i8, same work, registers only, zero operands:         %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma16_kernel<<<blocks, 256>>>(d_zero, iters, dout); })));
+    printf("mfma same, random int8 operands:                                               %5.0f TOPS\n",
+           tops(settled_ms([&] { mfma16_kernel<<<blocks, 256>>>(d_rand, iters, dout); })));
     printf("mfma random operands + 0.5 ds_read_b128 per MFMA:                              %5.0f TOPS\n",
            tops(settled_ms([&] { mfma_kernel<8, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
     printf("mfma random operands + 256 B per MFMA loaded from L2:                          %5.0f TOPS\n",
