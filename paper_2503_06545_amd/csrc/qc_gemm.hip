@@ -76,7 +76,7 @@ __device__ inline float gelu_tanh_f(float y) {
     // 0.5 y (1 + tanh(u)) = y / (1 + exp(-2u)),  u = sqrt(2/pi) (y + 0.044715 y^3)
     const float c1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;  // -2 sqrt(2/pi) log2(e)
     const float c2 = c1 * 0.044715f;
-    const float t = y * (c1 + c2 * (y * y));
+    const float t = y * fmaf(c2, y * y, c1);
     return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
