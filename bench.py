@@ -35,10 +35,10 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
 # FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this script, scaled by the same counters on a plain
 # 256 MiB copy (profiles/bench_<workload>_rocprofv3.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "qkv256": {"gemm": 165.9e6, "quant": 56.9e6, "delta": 33.6e6},
-    "fc1_512": {"gemm": 851.9e6, "quant": 226.9e6, "delta": 33.6e6},
-    "fc2_512_w8": {"gemm": 1034.0e6, "quant": 906.4e6, "delta": 33.6e6},
-    "fc2_512_w4": {"gemm": 772.0e6, "quant": 906.4e6, "delta": 33.6e6},
+    "qkv256": {"gemm": 165.5e6, "quant": 56.9e6, "delta": 33.6e6},
+    "fc1_512": {"gemm": 852.5e6, "quant": 226.9e6, "delta": 33.6e6},
+    "fc2_512_w8": {"gemm": 1304.7e6, "quant": 906.3e6, "delta": 33.6e6},
+    "fc2_512_w4": {"gemm": 814.8e6, "quant": 906.3e6, "delta": 33.6e6},
 }
 
 WORKLOADS = ("qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4", "sweep28")

@@ -10,6 +10,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <type_traits>
 #include <vector>
 
 #define CK(x)                                                                     \
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void read_kernel(const float4 *__restrict__ a,
 // global loads per wavefront from an L2-resident buffer.  VIA_LDS: those GLD loads are
 // direct-to-LDS copies into a ring private to the wavefront, each followed by a ds_read_b128 of
 // the same size (the reads race with the copies on purpose: only the traffic matters here).
-template <int LDSR, int GLD, bool VIA_LDS = false>
+template <int LDSR, int GLD, bool VIA_LDS = false, bool M16 = false>
 __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ data,
                                                       const uint8_t *__restrict__ gsrc, int iters,
                                                       int *out) {
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
     __syncthreads();
     uint8_t *ring = lds + 16384 + (threadIdx.x >> 6) * 8192;  // 8 slots of 1 KiB per wavefront
     const uint32_t ring_lane = (uint32_t)(uintptr_t)ring + (threadIdx.x & 63) * 16;
-    v16i acc[8];
+    v16i acc[8];   // as 16x16 tiles: acc[t] holds four of them
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -95,8 +96,19 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[t], acc[t], 0, 0, 0);
+            for (int t = 0; t < 8; ++t) {
+                if (M16) {  // the same multiply count as two 16x16x64 operations
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int q = 2 * i + h;
+                        v4i c = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+                        c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[t], c, 0, 0, 0);
+                        acc[t][4 * q] = c[0]; acc[t][4 * q + 1] = c[1]; acc[t][4 * q + 2] = c[2]; acc[t][4 * q + 3] = c[3];
+                    }
+                } else {
+                    acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[t], acc[t], 0, 0, 0);
+                }
+            }
         if (VIA_LDS) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
         for (int j = 0; j < GLD; ++j) gx ^= gl[j];
@@ -105,35 +117,6 @@ __global__ __launch_bounds__(256, 2) void mfma_kernel(const v4i *__restrict__ da
     int s = gx[0] ^ gx[1] ^ gx[2] ^ gx[3];
 #pragma unroll
     for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
-    if (s == 0x7fffffff) out[0] = s;
-}
-
-// The same amount of work per iteration with the 16x16x64 form of the instruction (32 MFMAs on a
-// 64x128 accumulator patch): twice the operand reads and the same accumulator traffic per MAC.
-__global__ __launch_bounds__(256, 2) void mfma16_kernel(const v4i *__restrict__ data, int iters,
-                                                        int *out) {
-    v4i acc[4][8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) acc[i][t] = v4i{0, 0, 0, 0};
-    v4i a[4], b[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] = data[(threadIdx.x * 4 + i) & 1023];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) b[i] = data[(threadIdx.x * 8 + i + 512) & 1023];
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-                acc[i][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[t], acc[i][t], 0, 0, 0);
-    }
-    int s = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) s += acc[i][t][0] + acc[i][t][3];
     if (s == 0x7fffffff) out[0] = s;
 }
 
@@ -270,24 +253,26 @@ int main() {
     const int iters = 20000, blocks = 2 * CU;
     const double ops = (double)blocks * 4 * iters * 16 * 65536.0;
     auto tops = [&](float ms) { return ops / ms * 1e-9; };
-    printf("mfma v_mfma_i32_32x32x32_i8, 2 wavefronts/SIMD, registers only, zero operands: %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_zero, gsrc, iters, dout); })));
-    printf("mfma same, random int8 operands:                                               %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<0, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-    printf("mfma v_mfma_i32_16x16x64_i8, same work, registers only, zero operands:         %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma16_kernel<<<blocks, 256>>>(d_zero, iters, dout); })));
-    printf("mfma same, random int8 operands:                                               %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma16_kernel<<<blocks, 256>>>(d_rand, iters, dout); })));
-    printf("mfma random operands + 0.5 ds_read_b128 per MFMA:                              %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<8, 0><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-    printf("mfma random operands + 256 B per MFMA loaded from L2:                          %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<0, 4><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-    printf("mfma random operands + 256 B per MFMA copied L2 -> LDS and read back from LDS:  %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<0, 4, true><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-    printf("mfma random operands + 0.5 ds_read_b128 and 384 B from L2 per MFMA (the GEMM): %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<8, 6><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-    printf("mfma random operands + 0.5 ds_read_b128 and 128 B from L2 per MFMA:            %5.0f TOPS\n",
-           tops(settled_ms([&] { mfma_kernel<8, 2><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    // Operand traffic is quoted per 32 K multiply-adds: one 32x32x32 or two 16x16x64 operations.
+    auto mfma_lines = [&](auto m16_tag, const char *form) {
+        constexpr bool M16 = decltype(m16_tag)::value;
+        printf("mfma %s, 2 wavefronts/SIMD, registers only, zero operands:  %5.0f TOPS\n", form,
+               tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_zero, gsrc, iters, dout); })));
+        printf("  random int8 operands:                                                 %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        printf("  random + 0.5 ds_read_b128 per 32 K multiply-adds:                     %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<8, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        printf("  random + 256 B loaded from L2:                                        %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<0, 4, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        printf("  random + 256 B copied L2 -> LDS and read back from LDS:               %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<0, 4, true, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        printf("  random + 0.5 ds_read_b128 and 384 B from L2 (the GEMM's proportions): %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<8, 6, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        printf("  random + 0.5 ds_read_b128 and 128 B from L2:                          %5.0f TOPS\n",
+               tops(settled_ms([&] { mfma_kernel<8, 2, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+    };
+    mfma_lines(std::false_type{}, "v_mfma_i32_32x32x32_i8");
+    mfma_lines(std::true_type{}, "v_mfma_i32_16x16x64_i8");
 
     {
         const int li = 20000;
