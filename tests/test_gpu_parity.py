@@ -309,6 +309,40 @@ def test_qlinear_is_deterministic_and_stays_inside_its_output():
     assert torch.all(buf[:pad] == -7.0) and torch.all(buf[pad + M * N:] == -7.0)
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N", [4, 8, 12, 129, 130, 132, 136, 260, 264])
+def test_qlinear_every_store_width_stays_inside_its_output(bits, N):
+    """A lane owns eight consecutive channels of a token and writes them as one 16 B store, two
+    8 B or 16 B stores or single elements, depending on N mod 8, N mod 4 and the output type:
+    every class, on a ragged M, against the oracle and with guard bands around Y."""
+    rng = np.random.default_rng(1000 * bits + N)
+    M, K = 300, 192
+    x = random_x(rng, M, K, "f32")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE["none"], 8)
+    xd, pw, bd = dev(x), qc.pack_weight_t(dev(W), bits), dev(b)
+    pad = 1024  # elements; keeps Y 16-byte aligned for every element size
+    for out, tdtype, fill in (("bf16", torch.bfloat16, -7.0), ("f32", torch.float32, -7.0),
+                              ("i32", torch.int32, -7)):
+        buf = torch.full((M * N + 2 * pad,), fill, dtype=tdtype, device="cuda")
+        Y = buf[pad:pad + M * N].view(M, N)
+        if out == "i32":
+            y = qc.qlinear_t(xd, pw, None, "none", out, Y=Y)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy(), ref["acc"]), out
+        else:
+            y = qc.qlinear_t(xd, pw, bd, "none", out, Y=Y)
+            torch.cuda.synchronize()
+            if out == "bf16":
+                y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(ref["y"]))
+            else:
+                y_ref = oracle.round_f32(ref["y"]).astype(np.float64)
+            assert_outputs_close(host_f64(y), y_ref, RTOL[out])
+        assert torch.all(buf[:pad] == fill) and torch.all(buf[pad + M * N:] == fill), out
+
+
 # ------------------------------------------------------------------ full-size configs, sampled rows
 
 def sampled_rows_case(case: synth.LinearCase, rows_wanted=96):
