@@ -343,6 +343,42 @@ def test_qlinear_every_store_width_stays_inside_its_output(bits, N):
         assert torch.all(buf[:pad] == fill) and torch.all(buf[pad + M * N:] == fill), out
 
 
+def test_step_replays_from_a_hip_graph():
+    """The library allocates nothing and clears nothing with memset calls, so one step (qc_qlinear
+    and qc_latent_delta with caller-owned workspaces) can be captured once and replayed.  Every
+    replay, with eager work and synchronizations in between, must give the eager bits."""
+    rng = np.random.default_rng(5)
+    M, K, N = 777, 1152, 392
+    x = dev(random_x(rng, M, K, "bf16"))
+    pw = qc.pack_weight_t(dev((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), 4)
+    b = dev((rng.standard_normal(N) * 0.01).astype(np.float32))
+    n = 1 << 20
+    cur, prev = (dev(a) for a in synth.latent_pair(seed=3, n=n))
+    ws, dws = qc.qlinear_workspace_t(M, K, N), qc.latent_delta_workspace_t(n)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    out3 = torch.empty(3, dtype=torch.float32, device="cuda")
+
+    def step():
+        qc.qlinear_t(x, pw, b, "gelu_tanh", "bf16", workspace=ws, Y=Y, act_bits=6)
+        qc.latent_delta_t(cur, prev, workspace=dws, out3=out3)
+
+    step()  # eager: also sets the kernels' attributes, which cannot be done while capturing
+    torch.cuda.synchronize()
+    y_ref, d_ref = Y.clone(), out3.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        Y.fill_(0)
+        out3.fill_(0)
+        ws.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y.view(torch.int16), y_ref.view(torch.int16))
+        assert torch.equal(out3.view(torch.int32), d_ref.view(torch.int32))
+
+
 # ------------------------------------------------------------------ full-size configs, sampled rows
 
 def sampled_rows_case(case: synth.LinearCase, rows_wanted=96):
