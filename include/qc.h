@@ -58,7 +58,9 @@ typedef enum { QC_OUT_F32 = 0, QC_OUT_BF16 = 1, QC_OUT_I32_ACC = 2 } qc_out;
 #define QC_MAX_PREV 8
 
 const char *qc_status_string(qc_status status);
-/* Library ABI version (major * 1000 + minor). */
+/* Library version (major * 1000 + minor).  The packed-weight blob and the workspaces are
+ * opaque and belong to the version that wrote them: the minor number changes whenever their
+ * internal order does (the blob's header carries a layout tag of its own). */
 int qc_version(void);
 
 /* ---- sizes (host, pure functions) ------------------------------------------------ */

@@ -19,7 +19,7 @@ extern "C" const char *qc_status_string(qc_status status) {
     return "unknown qc_status";
 }
 
-extern "C" int qc_version(void) { return 1002; }
+extern "C" int qc_version(void) { return 1003; }
 
 // ---- decision rules: host arithmetic only ---------------------------------------------------
 

@@ -37,7 +37,7 @@ def test_binding_constants_equal_the_header():
 
 
 def test_version_and_status_strings():
-    assert qc.qc_version() == 1002
+    assert qc.qc_version() == 1003
     assert qc.status_string(0) == "QC_OK"
     for s in range(1, 5):
         assert qc.status_string(s).startswith("QC_ERR_")
