@@ -343,6 +343,42 @@ def test_qlinear_every_store_width_stays_inside_its_output(bits, N):
         assert torch.all(buf[:pad] == fill) and torch.all(buf[pad + M * N:] == fill), out
 
 
+def test_calls_on_two_streams_do_not_disturb_each_other():
+    """The library keeps no device state of its own: two different linears issued on two
+    streams at the same time, each with its own workspace, give the bits they give alone."""
+    rng = np.random.default_rng(21)
+    jobs = []
+    for (M, K, N, bits, act_bits, epi) in ((3000, 1152, 1152, 8, 8, "none"), (2000, 2304, 640, 4, 6, "gelu_tanh")):
+        x = dev(random_x(rng, M, K, "bf16"))
+        pw = qc.pack_weight_t(dev((rng.standard_normal((N, K)) * 0.02).astype(np.float32)), bits)
+        b = dev((rng.standard_normal(N) * 0.01).astype(np.float32))
+        ws = qc.qlinear_workspace_t(M, K, N)
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        jobs.append(dict(x=x, pw=pw, b=b, ws=ws, Y=Y, epi=epi, act_bits=act_bits))
+
+    def run(j):
+        qc.qlinear_t(j["x"], j["pw"], j["b"], j["epi"], "bf16", workspace=j["ws"], Y=j["Y"],
+                     act_bits=j["act_bits"])
+
+    alone = []
+    for j in jobs:
+        run(j)
+        torch.cuda.synchronize()
+        alone.append(j["Y"].clone())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]  # default priority
+    for _ in range(10):
+        for j in jobs:
+            j["Y"].fill_(0)
+        torch.cuda.synchronize()
+        for j, st in zip(jobs, streams):
+            with torch.cuda.stream(st):
+                for _ in range(3):
+                    run(j)
+        torch.cuda.synchronize()
+        for j, ref in zip(jobs, alone):
+            assert torch.equal(j["Y"].view(torch.int16), ref.view(torch.int16))
+
+
 def test_step_replays_from_a_hip_graph():
     """The library allocates nothing and clears nothing with memset calls, so one step (qc_qlinear
     and qc_latent_delta with caller-owned workspaces) can be captured once and replayed.  Every
