@@ -198,8 +198,9 @@ qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int 
  *      q = clamp(rne(x / s) + z, 0, levels)          dequantized value  s * (q - z)
  * Weights stay symmetric, so
  *      Y[m, n] = act( s[m] w_scale[n] * sum_k (q[m, k] - z[m]) qw[n, k] + bias[n] ).
- * The GEMM runs on the signed bytes q - 2^(act_bits-1); the epilogue adds
- * (2^(act_bits-1) - z[m]) * w_row_sums[n] in binary32.  One-sided inputs (the post-GELU input
+ * The GEMM runs on the signed bytes q - h, with h = 128 for act_bits 8 and h = 0 for 6 and 4
+ * (those codes fit a signed byte as they are); the epilogue adds (h - z[m]) * w_row_sums[n] in
+ * binary32.  One-sided inputs (the post-GELU input
  * of the MLP's second linear) gain about one bit over the symmetric form.
  *
  *   qc_weight_row_sums   w_row_sums[n] = sum_k qw[n, k] (int32 [N], device, 16-byte aligned),
@@ -209,8 +210,8 @@ qc_status qc_qlinear_rot(const void *X, qc_dtype xdt, int64_t M, int64_t K, int 
  *                        with a narrow range has a zero point beyond int32).
  *   qc_qlinear_asym      quantize + GEMM + epilogue.  workspace >=
  *                        qc_qlinear_asym_workspace_bytes(M, K, N) bytes.  With QC_OUT_I32_ACC, Y
- *                        is sum_k (q[m, k] - 2^(act_bits-1)) qw[n, k], the sum the MFMA loop
- *                        forms on the stored bytes.
+ *                        is sum_k (q[m, k] - h) qw[n, k], the sum the MFMA loop forms on the
+ *                        stored bytes.
  *   qc_qlinear_asym_quant, qc_qlinear_asym_gemm   the two halves of qc_qlinear_asym as calls
  *                        of their own, as qc_qlinear_quant / qc_qlinear_gemm are of qc_qlinear.
  *   qc_debug_workspace_act_asym   test hook: the codes, scales and zero points

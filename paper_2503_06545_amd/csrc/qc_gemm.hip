@@ -54,7 +54,7 @@ struct StageLayout {
 struct GemmArgs {
     const uint8_t *x_tiled;
     const float *x_scale;   // Mp entries (padded), 16 B aligned
-    const float *x_corr;    // asymmetric activations only: per token 2^(b-1) - zero point, Mp entries
+    const float *x_corr;    // asymmetric activations only: per token code shift - zero point, Mp entries
     const int32_t *w_rowsum;  // asymmetric activations only: per channel sum of the weight codes
     const uint8_t *w_codes;
     const float *w_scale;
@@ -109,8 +109,8 @@ __device__ inline void tile_of_block(int b, int nblocks, int m_tiles, int n_tile
 #define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 #define QC_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
-// ASYM: the activation codes are the unsigned codes of the asymmetric quantizer minus 2^(b-1)
-// (Section 3.1 Eq. (3)-(4) as printed).  With c[m] = 2^(b-1) - z[m] the dequantized activation
+// ASYM: the activation codes are the unsigned codes of the asymmetric quantizer minus a shift h
+// (128 for 8-bit codes, else 0; Section 3.1 Eq. (3)-(4) as printed).  With c[m] = h - z[m] the dequantized activation
 // is sx (code + c), so the epilogue adds c[m] * sum_k qw[n, k] to the accumulator.
 template <int BITS, int OUT, int EPI, bool ASYM>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {

@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void weight_row_sums_kernel(const uint8_t
 }
 
 // The same for the workspace of the asymmetric linear: unsigned codes back from the stored
-// signed bytes (code - 2^(b-1)), zero point back from the stored correction 2^(b-1) - z.
+// signed bytes (code - shift), zero point back from the stored correction shift - z.
 __global__ __launch_bounds__(kThreads) void untile_act_asym_kernel(const uint8_t *__restrict__ tiled,
                                                                    const float *__restrict__ scales,
                                                                    const float *__restrict__ corr,
@@ -280,6 +280,6 @@ extern "C" qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t 
     const int64_t blocks = (M * K + kThreads - 1) / kThreads;
     untile_act_asym_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
         base + ws.codes_offset, (const float *)base, (const float *)(base + ws.corr_offset), M, K,
-        ws.sym.KF, 1 << (act_bits - 1), qx, x_scale, x_zero);
+        ws.sym.KF, asym_code_shift(act_bits), qx, x_scale, x_zero);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }

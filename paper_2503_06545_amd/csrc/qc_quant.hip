@@ -341,8 +341,8 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
 //   s = max(hi - lo, 2^-64) / levels,  z = -rne(lo / s),  code = clamp(rne(x / s) + z, 0, levels)
 // with levels = 2^b - 1.  Same layout and the same division-free quotient as above (it is
 // exact for these larger quotients as well, checked on the host).  `shifted` selects what is
-// stored: the canonical unsigned code and z, or, for the GEMM, code - 2^(b-1) as a signed byte
-// and the correction 2^(b-1) - z.
+// stored: the canonical unsigned code and z, or, for the GEMM, code - shift as a signed byte
+// and the correction shift - z (shift = asym_code_shift(act_bits)).
 template <typename XT>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, uint8_t *__restrict__ qx,
@@ -504,7 +504,7 @@ hipError_t launch_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t
                                  uint8_t *qx_tiled, int64_t KF, float *x_scale, float *x_aux,
                                  int act_bits, bool shifted, hipStream_t stream) {
     if (!quant_vector_path(K)) return hipErrorInvalidValue;  // the entry points reject these first
-    const float levels = (float)((1 << act_bits) - 1), shift = (float)(1 << (act_bits - 1));
+    const float levels = (float)((1 << act_bits) - 1), shift = (float)asym_code_shift(act_bits);
     const int64_t slices = (K / kUnit + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const dim3 grid((unsigned)((M + kRowsPerBlock - 1) / kRowsPerBlock)), block((unsigned)(64 * slices));
     if (xdt == QC_BF16)

@@ -697,7 +697,7 @@ def run_asym_case(x, W, b, bits, epi, out, act_bits=8):
     assert np.array_equal(qx.cpu().numpy(), ref["qx"]), "activation codes differ"
     # the MFMA loop's own sum, on the stored signed bytes
     acc = qc.qlinear_asym_t(xd, pw, rs, None, "none", "i32", workspace=ws, act_bits=act_bits)
-    shifted = (ref["qx"].astype(np.int16) - (1 << (act_bits - 1))).astype(np.int8)
+    shifted = (ref["qx"].astype(np.int16) - (128 if act_bits == 8 else 0)).astype(np.int8)
     assert np.array_equal(acc.cpu().numpy(), oracle.gemm_i32(shifted, qw_ref))
     y_ref = ref["y"]
     if out == "bf16":
