@@ -107,7 +107,6 @@ __device__ inline void tile_of_block(int b, int nblocks, int m_tiles, int n_tile
 
 // vmcnt(n) with the other counters left unconstrained (gfx9 encoding, n < 16)
 #define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
-#define QC_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
 // ASYM: the activation codes are the unsigned codes of the asymmetric quantizer minus a shift h
 // (128 for 8-bit codes, else 0; Section 3.1 Eq. (3)-(4) as printed).  With c[m] = h - z[m] the dequantized activation
