@@ -1,25 +1,48 @@
 // Latent change reduction (Section 3.2 HLC, Eq. (5)): sum|cur - prev| and sum|prev| in one
 // pass over both tensors, deterministic result.
 //
-// HBM-bound (8 bytes read per element, 12 bytes written in total).  Each lane reads 16 B per
-// load, sums four terms in binary32 and carries the running sums in binary64; wavefronts
-// combine by shuffles and every block leaves one partial pair.  A second, single-block launch
-// adds the partial pairs in index order, so the bits do not depend on scheduling.  (A single
-// launch that lets the last block to arrive do the combine was measured slower: the device-scope
-// arrival counter costs about 15 ns per block, more than the second launch.)
+// HBM-bound (8 bytes read per element, 12 bytes written in total).  The grid is at most one
+// block of 1024 threads per CU; a lane has four 16 B loads per tensor in flight (128 KiB per
+// CU), sums four terms in binary32 and carries the running sums in binary64.  Wavefronts
+// combine with DPP moves (no LDS round trips) and every block leaves one partial pair.  A
+// second, single-block launch adds the partial pairs in index order, so the bits do not depend
+// on scheduling.  Single-launch forms were measured and are not faster: the block that arrives
+// last has to see the others' partial sums, and on this chip (one L2 per XCD) that costs either
+// a release fence per block, which writes the L2 back (35 us for 1024 blocks), or stores and
+// arrival counters that go to memory and are waited for one after the other (2.3 us, what the
+// second launch costs).
 #include "qc_internal.h"
 
 namespace qc {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;       // combine kernels, variation pass
+constexpr int kWideThreads = 1024;  // streaming passes: 16 wavefronts per CU
 constexpr int kMaxBlocks = 256;     // one block per CU
 constexpr int kUnroll = 4;          // float4 loads in flight per tensor per lane
 
+// one DPP move of a binary64 value (two 32-bit halves); CTRL as in the ISA's dpp_ctrl field
+template <int CTRL>
+__device__ inline double dpp_move(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes, the same bits in every lane: butterflies inside a row of 16 lanes
+// (quad_perm [1,0,3,2], [2,3,0,1], row_half_mirror, row_mirror), then the four row sums in
+// index order.
 __device__ inline double wave_sum(double v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    double r[4];
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-    return v;
+    for (int i = 0; i < 4; ++i)
+        r[i] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 16 * i),
+                                __builtin_amdgcn_readlane(__double2loint(v), 16 * i));
+    return (r[0] + r[1]) + (r[2] + r[3]);
 }
 
 __device__ inline float abs4(const float4 &a, const float4 &b) {
@@ -29,53 +52,63 @@ __device__ inline float abs4(const float4 &b) {
     return (fabsf(b.x) + fabsf(b.y)) + (fabsf(b.z) + fabsf(b.w));
 }
 
-// block-wide sum of (num, den); result valid in thread 0
-__device__ inline void block_sum(double &num, double &den, double *sh) {
-    num = wave_sum(num);
-    den = wave_sum(den);
+// block-wide sums of COUNT values in wavefront order; result valid in thread 0.
+// sh holds COUNT * (THREADS / 64) doubles and may be reused after the call.
+template <int THREADS, int COUNT>
+__device__ inline void block_sum(double (&v)[COUNT], double *sh) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) { sh[2 * wave] = num; sh[2 * wave + 1] = den; }
+#pragma unroll
+    for (int c = 0; c < COUNT; ++c) {
+        v[c] = wave_sum(v[c]);
+        if (lane == 0) sh[COUNT * wave + c] = v[c];
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        num = sh[0]; den = sh[1];
 #pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) { num += sh[2 * w]; den += sh[2 * w + 1]; }
+        for (int c = 0; c < COUNT; ++c) {
+            double t = sh[c];
+            for (int w = 1; w < THREADS / 64; ++w) t += sh[COUNT * w + c];
+            v[c] = t;
+        }
     }
     __syncthreads();
 }
 
-__global__ __launch_bounds__(kThreads) void latent_delta_partial_kernel(
+// A block takes contiguous chunks of kWideThreads * kUnroll float4 (64 KiB per tensor) and
+// strides over the tensor by the grid; all of a chunk's loads are issued before the first use.
+__global__ __launch_bounds__(kWideThreads) void latent_delta_partial_kernel(
     const float *__restrict__ cur, const float *__restrict__ prev, int64_t n,
     double *__restrict__ partials) {
-    __shared__ double sh[2 * (kThreads / 64)];
+    __shared__ double sh[2 * (kWideThreads / 64)];
     const int64_t n4 = n / 4;
     const float4 *c4 = reinterpret_cast<const float4 *>(cur);
     const float4 *p4 = reinterpret_cast<const float4 *>(prev);
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    double num = 0.0, den = 0.0;
-
-    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    for (; i + (kUnroll - 1) * stride < n4; i += kUnroll * stride) {
+    constexpr int64_t kChunk = (int64_t)kWideThreads * kUnroll;
+    double s[2] = {0.0, 0.0};
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4; base += (int64_t)gridDim.x * kChunk) {
         float4 a[kUnroll], b[kUnroll];
+        bool ok[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) { a[u] = c4[i + u * stride]; b[u] = p4[i + u * stride]; }
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kWideThreads + threadIdx.x;
+            ok[u] = i < n4;
+            const int64_t j = ok[u] ? i : 0;   // a valid index either way
+            a[u] = c4[j];
+            b[u] = p4[j];
+        }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) { num += (double)abs4(a[u], b[u]); den += (double)abs4(b[u]); }
-    }
-    for (; i < n4; i += stride) {
-        const float4 a = c4[i], b = p4[i];
-        num += (double)abs4(a, b);
-        den += (double)abs4(b);
+        for (int u = 0; u < kUnroll; ++u)
+            if (ok[u]) { s[0] += (double)abs4(a[u], b[u]); s[1] += (double)abs4(b[u]); }
     }
     if (blockIdx.x == 0 && threadIdx.x < (int)(n - n4 * 4)) {  // up to 3 trailing elements
         const int64_t j = n4 * 4 + threadIdx.x;
-        num += (double)fabsf(cur[j] - prev[j]);
-        den += (double)fabsf(prev[j]);
+        s[0] += (double)fabsf(cur[j] - prev[j]);
+        s[1] += (double)fabsf(prev[j]);
     }
-    block_sum(num, den, sh);
+    block_sum<kWideThreads, 2>(s, sh);
     if (threadIdx.x == 0) {
-        partials[2 * blockIdx.x] = num;
-        partials[2 * blockIdx.x + 1] = den;
+        partials[2 * blockIdx.x] = s[0];
+        partials[2 * blockIdx.x + 1] = s[1];
     }
 }
 
@@ -83,13 +116,14 @@ __global__ __launch_bounds__(kThreads) void latent_delta_partial_kernel(
 __global__ __launch_bounds__(kThreads) void latent_delta_final_kernel(
     const double *__restrict__ partials, int count, float *__restrict__ out3) {
     __shared__ double sh[2 * (kThreads / 64)];
-    double num = 0.0, den = 0.0;
+    double s[2] = {0.0, 0.0};
     for (int b = threadIdx.x; b < count; b += kThreads) {
-        num += partials[2 * b];
-        den += partials[2 * b + 1];
+        s[0] += partials[2 * b];
+        s[1] += partials[2 * b + 1];
     }
-    block_sum(num, den, sh);
+    block_sum<kThreads, 2>(s, sh);
     if (threadIdx.x == 0) {
+        const double num = s[0], den = s[1];
         float rel;
         if (den > 0.0) rel = (float)(num / den);
         else rel = num > 0.0 ? __builtin_inff() : 0.0f;
@@ -128,22 +162,25 @@ struct Oct<uint16_t> {  // bf16 bit patterns
     }
 };
 
+// A block takes contiguous chunks of kWideThreads * 2 groups of eight elements.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
+__global__ __launch_bounds__(kWideThreads) void similarity_partial_kernel(
     const T *__restrict__ a, const T *__restrict__ b, int64_t n, double *__restrict__ partials) {
-    __shared__ double sh[3 * (kThreads / 64)];
+    __shared__ double sh[3 * (kWideThreads / 64)];
     const int64_t n8 = n / 8;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    double ab = 0.0, aa = 0.0, bb = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n8; i += 2 * stride) {
+    constexpr int64_t kChunk = (int64_t)kWideThreads * 2;
+    double s[3] = {0.0, 0.0, 0.0};  // <a,b>, <a,a>, <b,b>
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n8; base += (int64_t)gridDim.x * kChunk) {
         Oct<T> x[2], y[2];
-        const bool second = i + stride < n8;
-        x[0].load(a + 8 * i);
-        y[0].load(b + 8 * i);
-        if (second) { x[1].load(a + 8 * (i + stride)); y[1].load(b + 8 * (i + stride)); }
+        const int64_t i0 = base + threadIdx.x, i1 = i0 + kWideThreads;
+        const bool ok[2] = {i0 < n8, i1 < n8};
+        x[0].load(a + 8 * (ok[0] ? i0 : 0));
+        y[0].load(b + 8 * (ok[0] ? i0 : 0));
+        x[1].load(a + 8 * (ok[1] ? i1 : 0));
+        y[1].load(b + 8 * (ok[1] ? i1 : 0));
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            if (u == 1 && !second) break;
+            if (!ok[u]) continue;
             float pab[2] = {0.f, 0.f}, paa[2] = {0.f, 0.f}, pbb[2] = {0.f, 0.f};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {  // two 4-term binary32 sums each
@@ -152,9 +189,9 @@ __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
                 paa[e >> 2] += xv * xv;
                 pbb[e >> 2] += yv * yv;
             }
-            ab += (double)pab[0] + (double)pab[1];
-            aa += (double)paa[0] + (double)paa[1];
-            bb += (double)pbb[0] + (double)pbb[1];
+            s[0] += (double)pab[0] + (double)pab[1];
+            s[1] += (double)paa[0] + (double)paa[1];
+            s[2] += (double)pbb[0] + (double)pbb[1];
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < (int)(n - n8 * 8)) {  // up to 7 trailing elements
@@ -167,56 +204,33 @@ __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
             xv = a[j];
             yv = b[j];
         }
-        ab += (double)(xv * yv);
-        aa += (double)(xv * xv);
-        bb += (double)(yv * yv);
+        s[0] += (double)(xv * yv);
+        s[1] += (double)(xv * xv);
+        s[2] += (double)(yv * yv);
     }
-    ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) { sh[3 * wave] = ab; sh[3 * wave + 1] = aa; sh[3 * wave + 2] = bb; }
-    __syncthreads();
+    block_sum<kWideThreads, 3>(s, sh);
     if (threadIdx.x == 0) {
-        for (int w = 1; w < kThreads / 64; ++w) { sh[0] += sh[3 * w]; sh[1] += sh[3 * w + 1]; sh[2] += sh[3 * w + 2]; }
-        partials[3 * blockIdx.x] = sh[0];
-        partials[3 * blockIdx.x + 1] = sh[1];
-        partials[3 * blockIdx.x + 2] = sh[2];
+        partials[3 * blockIdx.x] = s[0];
+        partials[3 * blockIdx.x + 1] = s[1];
+        partials[3 * blockIdx.x + 2] = s[2];
     }
 }
 
 __global__ __launch_bounds__(kThreads) void similarity_final_kernel(
     const double *__restrict__ partials, int count, float *__restrict__ out4) {
     __shared__ double sh[3 * (kThreads / 64)];
-    double ab = 0.0, aa = 0.0, bb = 0.0;
+    double s[3] = {0.0, 0.0, 0.0};
     for (int b = threadIdx.x; b < count; b += kThreads) {
-        ab += partials[3 * b]; aa += partials[3 * b + 1]; bb += partials[3 * b + 2];
+        s[0] += partials[3 * b]; s[1] += partials[3 * b + 1]; s[2] += partials[3 * b + 2];
     }
-    ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) { sh[3 * wave] = ab; sh[3 * wave + 1] = aa; sh[3 * wave + 2] = bb; }
-    __syncthreads();
+    block_sum<kThreads, 3>(s, sh);
     if (threadIdx.x == 0) {
-        for (int w = 1; w < kThreads / 64; ++w) { sh[0] += sh[3 * w]; sh[1] += sh[3 * w + 1]; sh[2] += sh[3 * w + 2]; }
-        const double denom = sqrt(sh[1]) * sqrt(sh[2]);
-        out4[0] = (float)sh[0];
-        out4[1] = (float)sh[1];
-        out4[2] = (float)sh[2];
-        out4[3] = denom > 0.0 ? (float)(sh[0] / denom) : 0.0f;
+        const double denom = sqrt(s[1]) * sqrt(s[2]);
+        out4[0] = (float)s[0];
+        out4[1] = (float)s[1];
+        out4[2] = (float)s[2];
+        out4[3] = denom > 0.0 ? (float)(s[0] / denom) : 0.0f;
     }
-}
-
-// block-wide sum of one value; result valid in thread 0.  sh holds kThreads / 64 doubles.
-__device__ inline double block_sum1(double v, double *sh) {
-    v = wave_sum(v);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __syncthreads();
-    if (lane == 0) sh[wave] = v;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        v = sh[0];
-#pragma unroll
-        for (int w = 1; w < kThreads / 64; ++w) v += sh[w];
-    }
-    return v;
 }
 
 // ---- inter-frame gradient norm (Section 3.2 HLC, second factor of Eq. (5)) -----------------
@@ -230,53 +244,55 @@ __device__ inline float widen(uint16_t v) { return __uint_as_float((uint32_t)v <
 
 // VEC: inner is a multiple of 8, so both streams can be read 8 elements at a time.
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kThreads) void gradient_partial_kernel(
+__global__ __launch_bounds__(kWideThreads) void gradient_partial_kernel(
     const T *__restrict__ m, int64_t inner, int64_t n, double *__restrict__ partials) {
-    __shared__ double sh[kThreads / 64];
+    __shared__ double sh[kWideThreads / 64];
     const T *lo = m, *hi = m + inner;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const int64_t first = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    double ss = 0.0;
+    double s[1] = {0.0};
     int64_t done = 0;
     if constexpr (VEC) {
         const int64_t n8 = n / 8;
-        for (int64_t i = first; i < n8; i += 2 * stride) {
+        constexpr int64_t kChunk = (int64_t)kWideThreads * 2;
+        for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n8; base += (int64_t)gridDim.x * kChunk) {
             Oct<T> x[2], y[2];
-            const bool second = i + stride < n8;
-            x[0].load(lo + 8 * i);
-            y[0].load(hi + 8 * i);
-            if (second) { x[1].load(lo + 8 * (i + stride)); y[1].load(hi + 8 * (i + stride)); }
+            const int64_t i0 = base + threadIdx.x, i1 = i0 + kWideThreads;
+            const bool ok[2] = {i0 < n8, i1 < n8};
+            x[0].load(lo + 8 * (ok[0] ? i0 : 0));
+            y[0].load(hi + 8 * (ok[0] ? i0 : 0));
+            x[1].load(lo + 8 * (ok[1] ? i1 : 0));
+            y[1].load(hi + 8 * (ok[1] ? i1 : 0));
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                if (u == 1 && !second) break;
+                if (!ok[u]) continue;
                 float p[2] = {0.f, 0.f};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {  // two 4-term binary32 sums
                     const float d = y[u].get(e) - x[u].get(e);
                     p[e >> 2] += d * d;
                 }
-                ss += (double)p[0] + (double)p[1];
+                s[0] += (double)p[0] + (double)p[1];
             }
         }
         done = n8 * 8;
     }
-    for (int64_t j = done + first; j < n; j += stride) {
+    const int64_t stride = (int64_t)gridDim.x * kWideThreads;
+    for (int64_t j = done + (int64_t)blockIdx.x * kWideThreads + threadIdx.x; j < n; j += stride) {
         const float d = widen(hi[j]) - widen(lo[j]);
-        ss += (double)(d * d);
+        s[0] += (double)(d * d);
     }
-    ss = block_sum1(ss, sh);
-    if (threadIdx.x == 0) partials[blockIdx.x] = ss;
+    block_sum<kWideThreads, 1>(s, sh);
+    if (threadIdx.x == 0) partials[blockIdx.x] = s[0];
 }
 
 __global__ __launch_bounds__(kThreads) void gradient_final_kernel(
     const double *__restrict__ partials, int count, float *__restrict__ out2) {
     __shared__ double sh[kThreads / 64];
-    double ss = 0.0;
-    for (int b = threadIdx.x; b < count; b += kThreads) ss += partials[b];
-    ss = block_sum1(ss, sh);
+    double s[1] = {0.0};
+    for (int b = threadIdx.x; b < count; b += kThreads) s[0] += partials[b];
+    block_sum<kThreads, 1>(s, sh);
     if (threadIdx.x == 0) {
-        out2[0] = (float)ss;
-        out2[1] = (float)sqrt(ss);
+        out2[0] = (float)s[0];
+        out2[1] = (float)sqrt(s[0]);
     }
 }
 
@@ -285,31 +301,33 @@ __global__ __launch_bounds__(kThreads) void gradient_final_kernel(
 // tensor is read once, not once per distance.
 
 struct PrevList { const float *p[QC_MAX_PREV]; };
+constexpr int kVarThreads = 512;   // two wavefronts per SIMD: room for 2 (COUNT + 1) float4 per lane
 
 template <int COUNT>
-__global__ __launch_bounds__(kThreads) void variation_partial_kernel(
+__global__ __launch_bounds__(kVarThreads) void variation_partial_kernel(
     const float *__restrict__ cur, PrevList prevs, int64_t n, double *__restrict__ partials) {
-    __shared__ double sh[kThreads / 64];
+    __shared__ double sh[COUNT * (kVarThreads / 64)];
     const int64_t n4 = n / 4;
     const float4 *c4 = reinterpret_cast<const float4 *>(cur);
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    constexpr int64_t kChunk = (int64_t)kVarThreads * 2;
     double d[COUNT];
 #pragma unroll
     for (int c = 0; c < COUNT; ++c) d[c] = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += 2 * stride) {
-        const bool second = i + stride < n4;
-        const int64_t i1 = second ? i + stride : i;  // a valid index either way
-        const float4 a0 = c4[i], a1 = c4[i1];
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4; base += (int64_t)gridDim.x * kChunk) {
+        const int64_t i = base + threadIdx.x;
+        const bool first = i < n4, second = i + kVarThreads < n4;
+        const int64_t i0 = first ? i : 0, i1 = second ? i + kVarThreads : 0;  // valid either way
+        const float4 a0 = c4[i0], a1 = c4[i1];
         float4 b0[COUNT], b1[COUNT];
 #pragma unroll
         for (int c = 0; c < COUNT; ++c) {
             const float4 *p4 = reinterpret_cast<const float4 *>(prevs.p[c]);
-            b0[c] = p4[i];
+            b0[c] = p4[i0];
             b1[c] = p4[i1];
         }
 #pragma unroll
         for (int c = 0; c < COUNT; ++c) {
-            d[c] += (double)abs4(a0, b0[c]);
+            if (first) d[c] += (double)abs4(a0, b0[c]);
             if (second) d[c] += (double)abs4(a1, b1[c]);
         }
     }
@@ -318,10 +336,10 @@ __global__ __launch_bounds__(kThreads) void variation_partial_kernel(
 #pragma unroll
         for (int c = 0; c < COUNT; ++c) d[c] += (double)fabsf(cur[j] - prevs.p[c][j]);
     }
+    block_sum<kVarThreads, COUNT>(d, sh);
+    if (threadIdx.x == 0) {
 #pragma unroll
-    for (int c = 0; c < COUNT; ++c) {
-        const double t = block_sum1(d[c], sh);
-        if (threadIdx.x == 0) partials[(int64_t)blockIdx.x * QC_MAX_PREV + c] = t;
+        for (int c = 0; c < COUNT; ++c) partials[(int64_t)blockIdx.x * QC_MAX_PREV + c] = d[c];
     }
 }
 
@@ -330,12 +348,12 @@ __global__ __launch_bounds__(kThreads) void variation_final_kernel(
     __shared__ double sh[kThreads / 64];
     double total = 0.0;
     for (int c = 0; c < count; ++c) {
-        double v = 0.0;
-        for (int b = threadIdx.x; b < blocks; b += kThreads) v += partials[(int64_t)b * QC_MAX_PREV + c];
-        v = block_sum1(v, sh);
+        double v[1] = {0.0};
+        for (int b = threadIdx.x; b < blocks; b += kThreads) v[0] += partials[(int64_t)b * QC_MAX_PREV + c];
+        block_sum<kThreads, 1>(v, sh);
         if (threadIdx.x == 0) {
-            out[c] = (float)v;
-            total += v;
+            out[c] = (float)v[0];
+            total += v[0];
         }
     }
     if (threadIdx.x == 0) out[count] = (float)total;
@@ -344,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void variation_final_kernel(
 template <int COUNT>
 void launch_variation(const float *cur, const PrevList &prevs, int64_t n, double *partials,
                       unsigned blocks, hipStream_t stream) {
-    variation_partial_kernel<COUNT><<<dim3(blocks), dim3(kThreads), 0, stream>>>(cur, prevs, n, partials);
+    variation_partial_kernel<COUNT><<<dim3(blocks), dim3(kVarThreads), 0, stream>>>(cur, prevs, n, partials);
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -365,12 +383,12 @@ extern "C" qc_status qc_latent_delta(const float *cur, const float *prev, int64_
     if (!aligned(cur, 16) || !aligned(prev, 16) || !aligned(out3, 4) || !aligned(workspace, 256))
         return QC_ERR_INVALID_ARG;
     if (workspace_bytes < qc_latent_delta_workspace_bytes(n)) return QC_ERR_WORKSPACE;
-    // one float4 per tensor per lane per unrolled step; at most one block per CU
-    int64_t blocks = (n / 4 + (int64_t)kThreads * kUnroll - 1) / ((int64_t)kThreads * kUnroll);
+    // one chunk of kWideThreads * kUnroll float4 per block and pass; at most one block per CU
+    int64_t blocks = (n / 4 + (int64_t)kWideThreads * kUnroll - 1) / ((int64_t)kWideThreads * kUnroll);
     if (blocks < 1) blocks = 1;
     if (blocks > kMaxBlocks) blocks = kMaxBlocks;
     double *partials = (double *)workspace;
-    latent_delta_partial_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+    latent_delta_partial_kernel<<<dim3((unsigned)blocks), dim3(kWideThreads), 0, (hipStream_t)stream>>>(
         cur, prev, n, partials);
     if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
     latent_delta_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(
@@ -391,15 +409,15 @@ extern "C" qc_status qc_layer_similarity(const void *a, const void *b, qc_dtype 
     if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out4, 4) || !aligned(workspace, 256))
         return QC_ERR_INVALID_ARG;
     if (workspace_bytes < qc_layer_similarity_workspace_bytes(n)) return QC_ERR_WORKSPACE;
-    int64_t blocks = (n / 8 + (int64_t)kThreads * 2 - 1) / ((int64_t)kThreads * 2);
+    int64_t blocks = (n / 8 + (int64_t)kWideThreads * 2 - 1) / ((int64_t)kWideThreads * 2);
     if (blocks < 1) blocks = 1;
     if (blocks > kMaxBlocks) blocks = kMaxBlocks;
     double *partials = (double *)workspace;
     if (dt == QC_BF16)
-        similarity_partial_kernel<uint16_t><<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        similarity_partial_kernel<uint16_t><<<dim3((unsigned)blocks), dim3(kWideThreads), 0, (hipStream_t)stream>>>(
             (const uint16_t *)a, (const uint16_t *)b, n, partials);
     else
-        similarity_partial_kernel<float><<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
+        similarity_partial_kernel<float><<<dim3((unsigned)blocks), dim3(kWideThreads), 0, (hipStream_t)stream>>>(
             (const float *)a, (const float *)b, n, partials);
     if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
     similarity_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(partials, (int)blocks, out4);
@@ -421,12 +439,12 @@ extern "C" qc_status qc_frame_gradient_norm(const void *m, qc_dtype dt, int64_t 
     if (workspace_bytes < qc_frame_gradient_norm_workspace_bytes(frames, inner)) return QC_ERR_WORKSPACE;
     const int64_t n = (frames - 1) * inner;  // number of differences
     const bool vec = inner % 8 == 0;
-    const int64_t per_block = (int64_t)kThreads * (vec ? 16 : 4);
+    const int64_t per_block = (int64_t)kWideThreads * (vec ? 16 : 4);
     int64_t blocks = (n + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;
     if (blocks > kMaxBlocks) blocks = kMaxBlocks;
     double *partials = (double *)workspace;
-    const dim3 grid((unsigned)blocks), block(kThreads);
+    const dim3 grid((unsigned)blocks), block(kWideThreads);
     hipStream_t st = (hipStream_t)stream;
     if (dt == QC_BF16) {
         if (vec) gradient_partial_kernel<uint16_t, true><<<grid, block, 0, st>>>((const uint16_t *)m, inner, n, partials);
@@ -436,7 +454,7 @@ extern "C" qc_status qc_frame_gradient_norm(const void *m, qc_dtype dt, int64_t 
         else gradient_partial_kernel<float, false><<<grid, block, 0, st>>>((const float *)m, inner, n, partials);
     }
     if (hipGetLastError() != hipSuccess) return QC_ERR_DEVICE;
-    gradient_final_kernel<<<dim3(1), block, 0, st>>>(partials, (int)blocks, out2);
+    gradient_final_kernel<<<dim3(1), dim3(kThreads), 0, st>>>(partials, (int)blocks, out2);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
 }
 
@@ -457,7 +475,7 @@ extern "C" qc_status qc_cumulative_variation(const float *cur, const float *cons
         if (c < count && (!prevs[c] || !aligned(prevs[c], 16))) return QC_ERR_INVALID_ARG;
     }
     if (workspace_bytes < qc_cumulative_variation_workspace_bytes(n, count)) return QC_ERR_WORKSPACE;
-    int64_t blocks = (n / 4 + (int64_t)kThreads * 2 - 1) / ((int64_t)kThreads * 2);
+    int64_t blocks = (n / 4 + (int64_t)kVarThreads * 2 - 1) / ((int64_t)kVarThreads * 2);
     if (blocks < 1) blocks = 1;
     if (blocks > kMaxBlocks) blocks = kMaxBlocks;
     double *partials = (double *)workspace;

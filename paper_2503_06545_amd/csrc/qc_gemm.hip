@@ -22,8 +22,6 @@
 // panels out of the L2.
 #include <type_traits>
 
-#include <atomic>
-
 #include "qc_internal.h"
 
 namespace qc {
@@ -450,18 +448,9 @@ hipError_t launch_variant(const GemmArgs &args, hipStream_t stream) {
     using L = StageLayout<BITS>;
     constexpr int kLds = kStages * L::kBytes +
                          (kTileM + 2 * kTileN + (ASYM ? kTileM + kTileN : 0)) * (int)sizeof(float);
-    // The attribute belongs to the function on one device: set it once per device (setting it
-    // twice, as two threads racing here may, is harmless).
-    static std::atomic<uint64_t> configured{0};
-    int device = 0;
-    if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
-    const uint64_t bit = 1ull << (device & 63);
-    if (!(configured.load(std::memory_order_acquire) & bit)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, OUT, EPI, ASYM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured.fetch_or(bit, std::memory_order_release);
-    }
+    // far below the 64 KiB a kernel may use without an attribute, so the first launch of a
+    // variant needs no set-up call and can be captured into a graph like any other
+    static_assert(kLds <= 64 * 1024, "dynamic LDS beyond the default limit needs an attribute");
     const int blocks = args.m_tiles * args.n_tiles;
     gemm_kernel<BITS, OUT, EPI, ASYM><<<dim3((unsigned)blocks), dim3(kThreads), kLds, stream>>>(args);
     return hipGetLastError();
@@ -508,9 +497,6 @@ hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8
     // launches the blocks that share a token panel next to each other, so that they read it at
     // the same time (fc2, 9 channel tiles, K = 4608: 870 MB instead of 1370 MB fetched by the L2s).
     args.group_m = args.n_tiles <= 16 ? 2 : 8;
-#ifdef QC_LAB
-    if (const char *g = getenv("QC_LAB_GROUP_M")) args.group_m = atoi(g);
-#endif
     if (x_corr && w_rowsum)
         return bits == 8 ? launch_bits<8, true>(args, epi, ydt, stream)
                          : launch_bits<4, true>(args, epi, ydt, stream);

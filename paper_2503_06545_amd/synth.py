@@ -14,6 +14,8 @@ configurations without materialising the whole tensor twice.
 from __future__ import annotations
 
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -43,8 +45,12 @@ def normal_rows(seed: int, tensor_id: int, row0: int, row1: int, K: int) -> np.n
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """float32 -> bf16 bit patterns (uint16), round to nearest even (a storage cast)."""
     u = np.ascontiguousarray(x, np.float32).view(np.uint32)
-    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
-    return (rounded >> np.uint32(16)).astype(np.uint16)
+    r = u >> np.uint32(16)          # in-place steps: one temporary instead of five
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= np.uint32(16)
+    return r.astype(np.uint16)
 
 
 def outlier_columns(seed: int, K: int, count: int) -> np.ndarray:
@@ -93,10 +99,20 @@ class LinearCase:
         return to_bf16_bits(x) if self.x_dtype == "bf16" else x
 
     def x(self) -> np.ndarray:
-        """All of X, generated in row chunks to bound the temporaries."""
-        chunk = 8192
-        parts = [self.x_rows(r, min(self.M, r + chunk)) for r in range(0, self.M, chunk)]
-        return parts[0] if len(parts) == 1 else np.concatenate(parts, axis=0)
+        """All of X, generated in row chunks (bounded temporaries) on a few threads; the
+        chunks are whole row blocks, so the bits do not depend on how the work is split."""
+        chunk = 32 * ROW_BLOCK
+        starts = range(0, self.M, chunk)
+        if len(starts) == 1:
+            return self.x_rows(0, self.M)
+        out = np.empty((self.M, self.K), np.uint16 if self.x_dtype == "bf16" else np.float32)
+
+        def fill(r):
+            out[r:min(self.M, r + chunk)] = self.x_rows(r, min(self.M, r + chunk))
+
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            list(pool.map(fill, starts))
+        return out
 
     def weight(self, layer: int = 0) -> np.ndarray:
         """W float32 [N, K] ~ N(0, std 0.02)."""

@@ -398,12 +398,12 @@ def test_step_replays_from_a_hip_graph():
         qc.qlinear_t(x, pw, b, "gelu_tanh", "bf16", workspace=ws, Y=Y, act_bits=6)
         qc.latent_delta_t(cur, prev, workspace=dws, out3=out3)
 
-    step()  # eager: also sets the kernels' attributes, which cannot be done while capturing
-    torch.cuda.synchronize()
-    y_ref, d_ref = Y.clone(), out3.clone()
+    # Captured before anything in this test ran eagerly: no call needs a set-up step (an
+    # attribute, an allocation, a memset) that capture would refuse.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         step()
+    replays = []
     for _ in range(3):
         Y.fill_(0)
         out3.fill_(0)
@@ -411,16 +411,23 @@ def test_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(Y.view(torch.int16), y_ref.view(torch.int16))
-        assert torch.equal(out3.view(torch.int32), d_ref.view(torch.int32))
+        replays.append((Y.clone(), out3.clone()))
+    Y.fill_(0)
+    out3.fill_(0)
+    step()  # eager
+    torch.cuda.synchronize()
+    for y_g, d_g in replays:
+        assert torch.equal(y_g.view(torch.int16), Y.view(torch.int16))
+        assert torch.equal(d_g.view(torch.int32), out3.view(torch.int32))
 
 
 # ------------------------------------------------------------------ full-size configs, sampled rows
 
-def sampled_rows_case(case: synth.LinearCase, rows_wanted=96):
+def sampled_rows_case(case: synth.LinearCase, rows_wanted=96, layer=0, x=None):
     M, K, N = case.M, case.K, case.N
-    x = case.x()
-    W, b = case.weight(), case.bias()
+    if x is None:
+        x = case.x()
+    W, b = case.weight(layer), case.bias(layer)
     pw = qc.pack_weight_t(dev(W), case.bits)
     ws = qc.qlinear_workspace_t(M, K, N)
     xd = dev(x)
@@ -457,6 +464,35 @@ def test_config_fc1_gelu_512_sampled_rows():
 @pytest.mark.parametrize("case", [synth.FC2_512_W8, synth.FC2_512_W4], ids=["w8", "w4"])
 def test_config_fc2_512_sampled_rows(case):
     sampled_rows_case(case, rows_wanted=48)
+
+
+def _sweep_layer(kind, bits):
+    """(index, case) of the first layer of the 28-block sweep with this shape and weight
+    bit-width, as the seeded importance mask assigns them."""
+    for i, c in enumerate(synth.stdit_block_layers()):
+        if c.name.endswith("_" + kind) and c.bits == bits:
+            return i, c
+    raise AssertionError(f"the mask gives no {kind} layer at {bits} bits")
+
+
+_sweep_x = {}
+
+
+@pytest.mark.parametrize("kind,bits", [("out", 8), ("out", 4), ("qkv", 4), ("fc1", 4), ("fc2", 8),
+                                       ("fc2", 4)])
+def test_config_sweep28_sampled_rows(kind, bits):
+    """Layers of the 28-block sweep at its full M = 131072 (CFG batch 2), with the weights of
+    their own layer index: the shapes and bit-width mixes the single-layer configurations do
+    not reach (out-projection 1152 -> 1152, 4-bit QKV and fc1, M twice as large)."""
+    i, case = _sweep_layer(kind, bits)
+    assert case.M == 131072
+    key = (case.K, case.post_gelu, case.outliers)
+    if key not in _sweep_x:
+        _sweep_x.clear()             # at most one activation tensor (up to 1.2 GB) is kept
+        _sweep_x[key] = case.x()
+    sampled_rows_case(case, rows_wanted=48 if case.K > 2000 else 64, layer=i, x=_sweep_x[key])
+    if kind == "fc2" and bits == 4:
+        _sweep_x.clear()
 
 
 # ------------------------------------------------------------------ qc_latent_delta
