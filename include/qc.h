@@ -280,6 +280,22 @@ qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K, in
 qc_status qc_latent_delta(const float *cur, const float *prev, int64_t n, float *out3,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- qc_latent_delta without a workspace ------------------------------------------------------
+ * For callers that cannot allocate device memory or have none to hand over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result, bit for bit, as
+ * qc_latent_delta; the per-block partial sums go to a fixed array inside the library
+ * (4 KiB of device memory per GPU, held until the process ends) instead of a workspace.  The
+ * call allocates and frees nothing.  Its first call on a device asks the runtime for that
+ * device's address of the array (no allocation, no synchronisation).
+ *   n          at most QC_LATENT_DELTA_STATIC_MAX_N, else UNSUPPORTED
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU (different
+ * streams) race and give undefined results; calls on one stream are ordered by the stream.
+ * Nothing has to be cleared between calls: every partial sum the combine reads is written by
+ * the same call first.  Other arguments and errors as for qc_latent_delta (no WORKSPACE). */
+#define QC_LATENT_DELTA_STATIC_MAX_N ((int64_t)1 << 30)
+qc_status qc_latent_delta_static(const float *cur, const float *prev, int64_t n, float *out3,
+                                 void *stream);
+
 /* ---- cosine similarity of the features of consecutive layers -----------------------------
  * Section 3.3 SRAP, Eq. (9): S = <a, b> / (||a|| ||b||), the score the layer-pruning rule of
  * Eq. (10) thresholds.

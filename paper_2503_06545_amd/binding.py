@@ -34,7 +34,7 @@ EXPORTS = (
     "qc_qlinear_asym_workspace_bytes", "qc_weight_row_sums", "qc_quant_act_asym",
     "qc_qlinear_asym", "qc_debug_workspace_act_asym", "qc_qlinear_asym_quant",
     "qc_qlinear_asym_gemm", "qc_quant_act_tensor_workspace_bytes", "qc_quant_act_tensor",
-    "qc_qlinear_tensor_workspace_bytes", "qc_qlinear_tensor",
+    "qc_qlinear_tensor_workspace_bytes", "qc_qlinear_tensor", "qc_latent_delta_static",
 )
 
 
@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
+        L.qc_latent_delta_static.restype = i32
+        L.qc_latent_delta_static.argtypes = [vp, vp, i64, vp, vp]
         f32 = ctypes.c_float
         L.qc_qlinear_asym_workspace_bytes.restype = sz
         L.qc_qlinear_asym_workspace_bytes.argtypes = [i64, i64, i64]
@@ -225,6 +227,13 @@ def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
 
 def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) -> int:
     return int(lib().qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream))
+
+
+QC_LATENT_DELTA_STATIC_MAX_N = 1 << 30
+
+
+def qc_latent_delta_static(cur, prev, n, out3, stream=0) -> int:
+    return int(lib().qc_latent_delta_static(cur, prev, n, out3, stream))
 
 
 # ---- tensor helpers: allocate outputs with torch, pass addresses and the current stream ----

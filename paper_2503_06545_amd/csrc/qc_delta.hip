@@ -11,6 +11,8 @@
 // a release fence per block, which writes the L2 back (35 us for 1024 blocks), or stores and
 // arrival counters that go to memory and are waited for one after the other (2.3 us, what the
 // second launch costs).
+#include <atomic>
+
 #include "qc_internal.h"
 
 namespace qc {
@@ -394,6 +396,41 @@ extern "C" qc_status qc_latent_delta(const float *cur, const float *prev, int64_
     latent_delta_final_kernel<<<dim3(1), dim3(kThreads), 0, (hipStream_t)stream>>>(
         partials, (int)blocks, out3);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
+}
+
+// ---- qc_latent_delta for callers that cannot allocate ---------------------------------------
+// The per-block partial sums live in a file-scope device array instead of a caller's workspace.
+// `scratch` below is the host-side handle of that array, not a device address: host code asks
+// the runtime once per device for the address of that device's copy and uses only that.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)kMaxBlocks * 2 * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// device address of the current device's copy of `scratch`, resolved on first use
+qc_status static_scratch(void **out) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0) return QC_ERR_DEVICE;
+    if (device >= kMaxDevices) return QC_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QC_ERR_DEVICE;
+        g_scratch_ptr[device].store(p, std::memory_order_release);  // racing threads store the same value
+    }
+    *out = p;
+    return QC_OK;
+}
+}  // namespace
+
+extern "C" qc_status qc_latent_delta_static(const float *cur, const float *prev, int64_t n,
+                                            float *out3, void *stream) {
+    if (!cur || !prev || !out3 || n < 1) return QC_ERR_INVALID_ARG;
+    if (n > QC_LATENT_DELTA_STATIC_MAX_N) return QC_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    if (qc_status st = static_scratch(&ws); st != QC_OK) return st;
+    // every partial pair the second launch reads is written by the first: nothing to clear
+    return qc_latent_delta(cur, prev, n, out3, ws, kStaticScratchBytes, stream);
 }
 
 extern "C" size_t qc_layer_similarity_workspace_bytes(int64_t n) {
