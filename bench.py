@@ -2,26 +2,33 @@
 """Benchmark of the quantized-linear hot path on one MI355X.
 
 A step is one pass of the per-step hot path over one batch of seeded synthetic input.  The
-default workload is the STDiT QKV projection of a 256x256 video (X bf16 [16384, 1152],
-W int8 [3456, 1152], bf16 out): qc_qlinear (per-token activation quantization + int8 MFMA
-GEMM + dequant/bias epilogue) followed by qc_latent_delta on two [16, 4, 16, 64, 64] float
-latents.  `--workload` selects the other STDiT layers (fc1+GELU, fc2 with int8 or int4
-weights) or the 28-block sweep (112 qc_qlinear calls, per-layer bit-width from the seeded
-importance mask); `--variant` selects how the activations are quantized (lower bit-widths,
-rotation fused in, or the asymmetric form), the GEMM kernel being the same.  Weights are packed once before the timed region (an offline step of the
-method); the packing time is reported beside the result.  Inputs are resident in HBM when
-timing starts.
+default workload, and the headline of the JSON line, is the largest single-GPU configuration:
+the 28-block STDiT linear sweep at M = 131072 tokens (CFG batch 2 at 512x512), 112 qc_qlinear
+calls per step (per-token activation quantization + int8 MFMA GEMM + dequant/bias/GELU
+epilogue) with the per-layer weight bit-width from the seeded importance mask.  The same run
+then times the single-layer configurations (QKV 256x256, fc1 + GELU 512x512, fc2 512x512 with
+int8 and with int4 weights, each with qc_latent_delta on a second stream) and reports them
+under `configs`, each with its own GEMM-only and whole-call TOPS, quantization GB/s and
+roofline.  `--workload NAME` makes one of those the headline instead (then without the
+others); `--variant` selects how the activations are quantized.
 
-Prints ONE JSON line.  `value` = integer ops (2*M*N*K per layer) of the step divided by the
-step time.  `roofline` describes the dominant kernel (the GEMM), timed with HIP events around
-batches of its launches; `kernels` adds the HBM-bound kernels; `cpu_baseline` is the CPU
-oracle timed on this host's cores on a bounded row sample of the same workload.
+Before the library touches the GPU, the stand-alone micro-benchmark bench/qc_roofs runs as a
+child process and measures what this machine sustains (HBM streams, the int8 MFMA loop on random
+operands with and without the GEMM's operand traffic); every roofline carries the fraction of
+the nominal peak and of those measured roofs.  Before any timed region the GPU is loaded for a
+fixed time, whatever --warmup says, so that the clocks have ramped up.
+
+Weights are packed once before the timed region (an offline step of the method); inputs are
+resident in HBM when timing starts.  Prints ONE JSON line.  `value` = integer ops (2*M*N*K per
+layer) of the step divided by the step time.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -30,29 +37,119 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, 8 TB/s
+PRELOAD_SECONDS = 0.3     # load on the GPU before every timed region, independent of --warmup
 
-# Bytes per launch between L2 and the fabric (Infinity Cache / HBM) from `rocprofv3 --pmc
-# FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this script, scaled by the same counters on a plain
-# 256 MiB copy (profiles/bench_<workload>_rocprofv3.txt).
-MEASURED_TRAFFIC_BYTES = {
-    "qkv256": {"gemm": 165.5e6, "quant": 56.9e6, "delta": 33.6e6},
-    "fc1_512": {"gemm": 852.5e6, "quant": 226.9e6, "delta": 33.6e6},
-    "fc2_512_w8": {"gemm": 1304.7e6, "quant": 906.3e6, "delta": 33.6e6},
-    "fc2_512_w4": {"gemm": 814.8e6, "quant": 906.3e6, "delta": 33.6e6},
-}
-
-WORKLOADS = ("qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4", "sweep28")
+SINGLE = ("qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4")
+WORKLOADS = ("sweep28",) + SINGLE
 # How the activations are quantized: the spec form (symmetric int8 per token), the lower
 # activation bit-widths of Eq. (8), the rotation fused into the quantization, or the printed
 # asymmetric form of Eq. (3)-(4).  The GEMM is the same kernel in all of them.
 VARIANTS = {"a8": dict(act_bits=8), "a6": dict(act_bits=6), "a4": dict(act_bits=4),
             "rot128": dict(act_bits=8, rot=128), "asym": dict(act_bits=8, asym=True)}
+VARIANT_TEXT = {"a8": "symmetric int8 per token", "a6": "symmetric 6 bit per token",
+                "a4": "symmetric 4 bit per token",
+                "rot128": "Walsh-Hadamard blocks of 128 columns, then symmetric int8 per token",
+                "asym": "asymmetric uint8 per token with zero point"}
+DESCRIBE = {
+    "sweep28": "28 STDiT blocks x (QKV 1152->3456, out 1152->1152, fc1 1152->4608 + GELU, "
+               "fc2 4608->1152), M = 131072 tokens (CFG batch 2 at 512x512), bf16 in/out, "
+               "per-layer weight bit-width from the seeded mask (BASELINE configs[4])",
+    "qkv256": "STDiT QKV projection 256x256 (BASELINE configs[1]): X bf16 [16384,1152] N(0,1) with "
+              "12 outlier columns x20, W8A8 [3456,1152], bias, bf16 out; + latent delta on "
+              "2 x [16,4,16,64,64] fp32",
+    "fc1_512": "STDiT MLP fc1 + GELU(tanh) 512x512 (BASELINE configs[2]): X bf16 [65536,1152], "
+               "W8A8 [4608,1152], bf16 out; + latent delta on 2 x [16,4,16,64,64] fp32",
+    "fc2_512_w8": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] post-GELU, "
+                  "W8A8 [1152,4608], bf16 out; + latent delta on 2 x [16,4,16,64,64] fp32",
+    "fc2_512_w4": "STDiT MLP fc2 512x512 (BASELINE configs[3]): X bf16 [65536,4608] post-GELU, "
+                  "W4A8 [1152,4608] int4 weights, bf16 out; + latent delta on 2 x [16,4,16,64,64] fp32",
+}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
 
+
+# ---- measured roofs, provenance ------------------------------------------------------------
+
+def measured_roofs():
+    """Run bench/qc_roofs --quick as a child process (it must finish before this process uses
+    the GPU) and return its "@key value" lines."""
+    exe = os.path.join(ROOT, "bench", "qc_roofs")
+    if not os.path.exists(exe):
+        return {"error": "bench/qc_roofs is not built (python -m paper_2503_06545_amd.build)"}
+    t0 = time.perf_counter()
+    try:
+        r = subprocess.run([exe, "--quick"], capture_output=True, text=True, timeout=120)
+    except subprocess.TimeoutExpired:
+        return {"error": "bench/qc_roofs --quick did not finish in 120 s"}
+    if r.returncode != 0:
+        return {"error": f"bench/qc_roofs exited with {r.returncode}: {r.stdout[-300:]}"}
+    out = {}
+    for line in r.stdout.splitlines():
+        if line.startswith("@"):
+            k, v = line[1:].split()
+            out[k] = float(v)
+    out["seconds"] = round(time.perf_counter() - t0, 1)
+    out["source"] = "bench/qc_roofs --quick, child process of this run, same GPU"
+    return out
+
+
+def traffic_table():
+    """HBM-side bytes per launch from the tracked rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE passes scaled by a plain copy): {workload: {kernel: bytes}}, the commit it was
+    measured at."""
+    table, commit = {}, None
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                p = line.split()
+                if len(p) >= 2 and p[0] == "measured_at_commit":
+                    commit = p[1]
+                elif len(p) == 4 and p[0] == "traffic":
+                    table.setdefault(p[1], {})[p[2]] = float(p[3])
+    except OSError:
+        pass
+    return table, commit
+
+
+def provenance():
+    import torch
+    h = hashlib.sha256()
+    files = ["bench.py", "include/qc.h"] + sorted(
+        os.path.join("paper_2503_06545_amd", "csrc", f)
+        for f in os.listdir(os.path.join(ROOT, "paper_2503_06545_amd", "csrc")))
+    for f in files:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            h.update(fh.read())
+    head = None
+    try:
+        r = subprocess.run(["git", "-C", ROOT, "describe", "--always", "--dirty", "--abbrev=12"],
+                           capture_output=True, text=True, timeout=10)
+        head = r.stdout.strip() or None
+    except (OSError, subprocess.TimeoutExpired):
+        pass
+    if head is None:  # the GPU box gets the tree without its history: take the build's stamp
+        try:
+            with open(os.path.join(ROOT, "paper_2503_06545_amd", "_build", "build_info.json")) as f:
+                head = json.load(f).get("git") + " (at build time)"
+        except (OSError, ValueError, TypeError):
+            pass
+    rocm = None
+    try:
+        with open("/opt/rocm/.info/version") as f:
+            rocm = f.read().strip()
+    except OSError:
+        pass
+    return {"git": head, "source_sha16": h.hexdigest()[:16],
+            "source_sha16_of": "bench.py, include/qc.h, paper_2503_06545_amd/csrc/*",
+            "rocm": rocm, "torch": torch.__version__, "hip": torch.version.hip}
+
+
+# ---- timing helpers ---------------------------------------------------------------------------
 
 def batch_times_us(fn, batch, rounds):
     """Average duration of one fn() from HIP events around batches of back-to-back calls
     (a batch keeps the GPU loaded and amortises the dispatch gap that an event pair around a
-    single launch would include)."""
+    single launch would include).  The events are recorded on torch's current stream, which is
+    the stream every timed kernel is launched on."""
     import torch
     t = []
     for _ in range(rounds):
@@ -66,53 +163,18 @@ def batch_times_us(fn, batch, rounds):
     return {"avg_us": sum(t) / len(t), "min_us": min(t)}
 
 
-def cpu_baseline(case, act_bits=8, rot=0, asym=False, target_seconds=15.0):
-    """The oracle as it stands on a bounded sample of token rows (all N, all K)."""
-    import oracle
-    W, b = case.weight(), case.bias()
-    qw, sw = oracle.quant_weight_rot(W, case.bits, rot) if rot else oracle.quant_weight(W, case.bits)
-    epi = {"none": oracle.EPI_NONE, "gelu_tanh": oracle.EPI_GELU_TANH,
-           "gelu_erf": oracle.EPI_GELU_ERF}[case.epi]
-
-    def linear(x):
-        if asym:
-            return oracle.qlinear_asym(x, qw, sw, b, epi, act_bits)
-        if rot:
-            return oracle.qlinear_rot(x, qw, sw, rot, b, epi, act_bits)
-        return oracle.qlinear(x, qw, sw, b, epi, act_bits)
-
-    threads = oracle.num_threads()
-    probe_rows = 64
-    x = case.x_rows(0, probe_rows)
+def preload(fn, seconds=PRELOAD_SECONDS):
+    """Keep the GPU busy with fn() for a fixed time so that its clocks have ramped up."""
+    import torch
     t0 = time.perf_counter()
-    linear(x)
-    per_row = (time.perf_counter() - t0) / probe_rows
-    rows = int(min(case.M, max(probe_rows, target_seconds / per_row)))
-    rows -= rows % 64
-    x = case.x_rows(0, rows)
-    # about 10 s of wall time on all host cores: the sample is repeated if one pass is shorter
-    reps, dt = 0, 0.0
-    while reps == 0 or (dt < 10.0 and reps < 50):
-        t0 = time.perf_counter()
-        linear(x)
-        dt += time.perf_counter() - t0
-        reps += 1
-    tops = 2.0 * reps * rows * case.N * case.K / dt / 1e12
-    # the same oracle on one thread, on a sixteenth of the sample
-    one_rows = max(64, rows // 16 - (rows // 16) % 64)
-    x1 = case.x_rows(0, one_rows)
-    oracle.set_num_threads(1)
-    t0 = time.perf_counter()
-    linear(x1)
-    dt1 = time.perf_counter() - t0
-    oracle.set_num_threads(threads)
-    one_thread = 2.0 * one_rows * case.N * case.K / dt1 / 1e12
-    return {"value": tops, "unit": "TOPS", "cores": threads, "kind": "oracle",
-            "one_thread": {"value": one_thread, "rows": one_rows, "seconds": dt1},
-            "sample": f"first {rows} of {case.M} token rows x all N={case.N} x K={case.K} of "
-                      f"layer {case.name} (quantize + int32 GEMM + epilogue), {reps} passes in "
-                      f"{dt:.2f} s, OpenMP over rows",
-            "seconds": dt}
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        fn()
+        n += 1
+        if n % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    return n
 
 
 class PowerSampler:
@@ -165,6 +227,105 @@ class PowerSampler:
                 "shader_clock_mhz_avg": avg(self.clock), "samples": len(self.power)}
 
 
+# ---- CPU baseline: the oracle as it stands -----------------------------------------------------
+
+def _oracle_linear(case, layer, act_bits, rot, asym):
+    import oracle
+    W, b = case.weight(layer), case.bias(layer)
+    qw, sw = oracle.quant_weight_rot(W, case.bits, rot) if rot else oracle.quant_weight(W, case.bits)
+    epi = {"none": oracle.EPI_NONE, "gelu_tanh": oracle.EPI_GELU_TANH,
+           "gelu_erf": oracle.EPI_GELU_ERF}[case.epi]
+
+    def linear(x):
+        if asym:
+            return oracle.qlinear_asym(x, qw, sw, b, epi, act_bits)
+        if rot:
+            return oracle.qlinear_rot(x, qw, sw, rot, b, epi, act_bits)
+        return oracle.qlinear(x, qw, sw, b, epi, act_bits)
+    return linear
+
+
+def cpu_baseline_layer(case, act_bits=8, rot=0, asym=False, target_seconds=12.0, layer=0):
+    """The oracle on a bounded sample of token rows (all N, all K) of one layer."""
+    import oracle
+    linear = _oracle_linear(case, layer, act_bits, rot, asym)
+    threads = oracle.num_threads()
+    probe_rows = 64
+    x = case.x_rows(0, probe_rows)
+    t0 = time.perf_counter()
+    linear(x)
+    per_row = (time.perf_counter() - t0) / probe_rows
+    rows = int(min(case.M, max(probe_rows, target_seconds / per_row)))
+    rows -= rows % 64
+    x = case.x_rows(0, rows)
+    reps, dt = 0, 0.0
+    while reps == 0 or (dt < 0.8 * target_seconds and reps < 50):
+        t0 = time.perf_counter()
+        linear(x)
+        dt += time.perf_counter() - t0
+        reps += 1
+    tops = 2.0 * reps * rows * case.N * case.K / dt / 1e12
+    # the same oracle on one thread, on a sixteenth of the sample
+    one_rows = max(64, rows // 16 - (rows // 16) % 64)
+    x1 = case.x_rows(0, one_rows)
+    oracle.set_num_threads(1)
+    t0 = time.perf_counter()
+    linear(x1)
+    dt1 = time.perf_counter() - t0
+    oracle.set_num_threads(threads)
+    one_thread = 2.0 * one_rows * case.N * case.K / dt1 / 1e12
+    return {"value": tops, "unit": "TOPS", "cores": threads, "kind": "oracle",
+            "one_thread": {"value": one_thread, "rows": one_rows, "seconds": dt1},
+            "sample": f"first {rows} of {case.M} token rows x all N={case.N} x K={case.K} of "
+                      f"layer {case.name} (quantize + int32 GEMM + epilogue), {reps} passes in "
+                      f"{dt:.2f} s, OpenMP over rows",
+            "seconds": dt}
+
+
+def cpu_baseline_sweep(cases, act_bits, rot, asym, target_seconds=20.0):
+    """The oracle on a row sample of one layer of each distinct (shape, weight bits) class of
+    the sweep; the classes' rates are combined with the number of layers of each class."""
+    import oracle
+    classes = {}
+    for i, c in enumerate(cases):
+        classes.setdefault((c.K, c.N, c.bits, c.epi), []).append(i)
+    threads = oracle.num_threads()
+    t_start = time.perf_counter()
+    per_class, total_ops, total_seconds, parts = [], 0.0, 0.0, []
+    budget = target_seconds / len(classes)
+    for (K, N, bits, epi), idx in classes.items():
+        case, layer = cases[idx[0]], idx[0]
+        linear = _oracle_linear(case, layer, act_bits, rot, asym)
+        x = case.x_rows(0, 64)
+        t0 = time.perf_counter()
+        linear(x)
+        per_row = (time.perf_counter() - t0) / 64
+        rows = int(min(case.M, max(64, 0.7 * budget / per_row)))
+        rows -= rows % 64
+        x = case.x_rows(0, rows)
+        t0 = time.perf_counter()
+        linear(x)
+        dt = time.perf_counter() - t0
+        sec_per_layer = dt / rows * case.M           # extrapolated to all M rows
+        total_seconds += sec_per_layer * len(idx)
+        total_ops += 2.0 * case.M * N * K * len(idx)
+        per_class.append({"K": K, "N": N, "weight_bits": bits, "epilogue": epi, "layers": len(idx),
+                          "rows": rows, "seconds": round(dt, 3),
+                          "tops": round(2.0 * rows * N * K / dt / 1e12, 5)})
+        parts.append(f"{rows} rows of {case.name}")
+    return {"value": total_ops / total_seconds / 1e12, "unit": "TOPS", "cores": threads,
+            "kind": "oracle",
+            "sample": "one layer of each of the sweep's " + str(len(classes)) + " (shape, weight bits) "
+                      "classes on its first rows (all N, all K; quantize + int32 GEMM + epilogue; "
+                      "OpenMP over rows): " + ", ".join(parts) + "; rows are independent, so each "
+                      "class's time is scaled to M = " + str(cases[0].M) + " rows and weighted by its "
+                      "number of layers (extrapolated)",
+            "extrapolated_seconds_per_step": round(total_seconds, 1),
+            "classes": per_class, "seconds": round(time.perf_counter() - t_start, 2)}
+
+
+# ---- the workloads ---------------------------------------------------------------------------------
+
 class Layer:
     """Device buffers of one quantized linear."""
 
@@ -180,19 +341,320 @@ class Layer:
         self.ops = 2.0 * case.M * case.N * case.K
 
 
+class Bench:
+    """Everything that is shared between the workloads of one run."""
+
+    def __init__(self, variant, roofs):
+        import torch
+        from paper_2503_06545_amd import binding as qc
+        from paper_2503_06545_amd import synth
+        self.torch, self.qc, self.synth = torch, qc, synth
+        var = VARIANTS[variant]
+        self.variant = variant
+        self.act_bits, self.rot, self.asym = var["act_bits"], var.get("rot", 0), var.get("asym", False)
+        self.roofs = roofs
+        self.traffic, self.traffic_commit = traffic_table()
+        self.stream = torch.cuda.current_stream().cuda_stream
+        # The latent change does not depend on the linear: a step issues it on a second stream
+        # (default priority) so that this HBM-bound reduction runs beside the GEMM.
+        self.side = torch.cuda.Stream()
+        self.x_dev = {}       # (K, post_gelu) -> device activations, the longest M asked for
+        cur_h, prev_h = synth.latent_pair(seed=0)
+        self.cur, self.prev = torch.from_numpy(cur_h).cuda(), torch.from_numpy(prev_h).cuda()
+        self.n_lat = self.cur.numel()
+        self.dws = qc.latent_delta_workspace_t(self.n_lat)
+        self.out3 = torch.empty(3, dtype=torch.float32, device="cuda")
+
+    # -- inputs: the single-layer configurations are row prefixes of the sweep's tensors (the
+    #    generator is keyed by row block), so one tensor per (K, distribution) serves them all
+    def activations(self, case):
+        import dataclasses
+        import numpy as np
+        key = (case.K, case.post_gelu, case.outliers, case.seed)
+        if key not in self.x_dev or self.x_dev[key].shape[0] < case.M:
+            bits = dataclasses.replace(case, x_dtype="bf16").x()
+            self.x_dev[key] = self.torch.from_numpy(bits.view(np.int16)).cuda().view(self.torch.bfloat16)
+        return self.x_dev[key][:case.M]
+
+    def check(self, st):
+        if st != self.qc.QC_OK:
+            raise self.qc.QcError(st, "bench step")
+
+    # -- the calls
+    def qlinear(self, L):
+        qc, c = self.qc, L.case
+        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16,
+                L.ws.data_ptr(), L.ws.numel(), self.stream)
+        head = (L.x.data_ptr(), qc.QC_BF16, c.M, c.K)
+        if self.asym:
+            self.check(qc.qc_qlinear_asym(*head, self.act_bits, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
+                                          L.row_sums.data_ptr(), *tail))
+        elif self.rot:
+            self.check(qc.qc_qlinear_rot(*head, self.act_bits, self.rot, L.pw.blob.data_ptr(),
+                                         L.pw.scale.data_ptr(), *tail))
+        elif self.act_bits != 8:
+            self.check(qc.qc_qlinear_act_bits(*head, self.act_bits, L.pw.blob.data_ptr(),
+                                              L.pw.scale.data_ptr(), *tail))
+        else:
+            self.check(qc.qc_qlinear(*head, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
+
+    def quant_stage(self, L, x=None):
+        qc, c = self.qc, L.case
+        head = ((L.x if x is None else x).data_ptr(), qc.QC_BF16, c.M, c.K)
+        tail = (L.ws.data_ptr(), L.ws.numel(), self.stream)
+        if self.asym:
+            self.check(qc.qc_qlinear_asym_quant(*head, self.act_bits, *tail))
+        elif self.rot:
+            self.check(qc.qc_qlinear_quant_rot(*head, self.act_bits, self.rot, *tail))
+        else:
+            self.check(qc.qc_qlinear_quant_bits(*head, self.act_bits, *tail))
+
+    def gemm_stage(self, L):
+        qc, c = self.qc, L.case
+        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16, self.stream)
+        if self.asym:
+            self.check(qc.qc_qlinear_asym_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
+                                               L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
+                                               L.row_sums.data_ptr(), *tail))
+        else:
+            self.check(qc.qc_qlinear_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
+                                          L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
+
+    def delta_stage(self, on=None, pair=None):
+        a, b = pair if pair is not None else (self.cur, self.prev)
+        self.check(self.qc.qc_latent_delta(a.data_ptr(), b.data_ptr(), self.n_lat, self.out3.data_ptr(),
+                                           self.dws.data_ptr(), self.dws.numel(),
+                                           self.stream if on is None else on))
+
+    def pack_stage(self, L):
+        qc, c = self.qc, L.case
+        if self.rot:
+            self.check(qc.qc_pack_weight_rot(L.W.data_ptr(), c.N, c.K, c.bits, self.rot,
+                                             L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), self.stream))
+        else:
+            self.check(qc.qc_pack_weight(L.W.data_ptr(), c.N, c.K, c.bits, L.pw.blob.data_ptr(),
+                                         L.pw.scale.data_ptr(), self.stream))
+
+    # -- rooflines
+    def mfma_roofline(self, name, kernel_name, ops, gemm_us, launches):
+        tops = ops / (gemm_us * 1e-6) / 1e12
+        r = {"bound": "mfma", "kernel": kernel_name, "achieved": round(tops, 1),
+             "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": round(tops / PEAK_INT8_TOPS, 4),
+             "traffic": self.traffic.get(name, {}).get("gemm") if self.variant == "a8" else None,
+             "traffic_source": ("profiles/hbm_traffic_per_launch.txt: rocprofv3 --pmc FETCH_SIZE / "
+                                "WRITE_SIZE passes of this script at commit " + str(self.traffic_commit) +
+                                ", not a measurement of this run"),
+             "ops_per_launch": ops / launches, "launches_per_step": launches,
+             "avg_launch_us": round(gemm_us / launches, 2)}
+        rand, fed = self.roofs.get("mfma_16x16x64_random_tops"), self.roofs.get("mfma_16x16x64_gemm_traffic_tops")
+        r["achievable"] = {
+            "mfma_registers_only_random_operands": rand,
+            "mfma_with_the_gemms_operand_traffic": fed,
+            "note": "measured in this run by bench/qc_roofs: the v_mfma_i32_16x16x64_i8 loop on random "
+                    "int8 operands held in registers, and the same loop fed 0.5 LDS fragment reads "
+                    "and 384 B from L2 per 32 K multiply-adds (the GEMM's proportions; a yardstick, "
+                    "not a bound)"}
+        r["frac_of_achievable"] = round(tops / rand, 4) if rand else None
+        r["frac_of_traffic_yardstick"] = round(tops / fed, 4) if fed else None
+        return r
+
+    def hbm_entry(self, bytes_per_launch, us, roof_key="hbm_copy_gbs", traffic=None):
+        gbs = bytes_per_launch / (us * 1e-6) / 1e9
+        roof = self.roofs.get(roof_key)
+        return {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": bytes_per_launch,
+                "avg_launch_us": round(us, 2), "traffic": traffic,
+                "achievable": roof, "achievable_is": roof_key + " of bench/qc_roofs, this run",
+                "frac_of_achievable": round(gbs / roof, 4) if roof else None}
+
+    # -- one single-layer configuration: qc_qlinear + qc_latent_delta on a second stream
+    def run_single(self, name, steps, warmup, with_cold=True):
+        torch, qc, synth = self.torch, self.qc, self.synth
+        case = {"qkv256": synth.QKV_256, "fc1_512": synth.FC1_512, "fc2_512_w8": synth.FC2_512_W8,
+                "fc2_512_w4": synth.FC2_512_W4}[name]
+        x = self.activations(case)
+        ws = (qc.qlinear_asym_workspace_t if self.asym else qc.qlinear_workspace_t)(case.M, case.K, case.N)
+        Y = torch.empty(case.M * case.N, dtype=torch.bfloat16, device="cuda")
+        L = Layer(case, x, ws, Y, 0, self.rot, self.asym)
+
+        def step():
+            self.qlinear(L)
+            self.delta_stage(self.side.cuda_stream)
+
+        preload(step)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        with PowerSampler() as sampler:
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+        device = sampler.summary()
+        value = L.ops / (ms_per_step * 1e-3) / 1e12
+
+        batch = 20
+        rounds = max(3, min(steps, 400) // batch)
+        preload(step, 0.1)
+        quant = batch_times_us(lambda: self.quant_stage(L), batch, rounds)
+        gemm = batch_times_us(lambda: self.gemm_stage(L), batch, rounds)
+        delta = batch_times_us(self.delta_stage, batch, rounds)
+        pack = batch_times_us(lambda: self.pack_stage(L), 1, 5)
+        tr = self.traffic.get(name, {}) if self.variant == "a8" else {}
+        quant_bytes = case.M * case.K * 3 + 4 * case.M
+        delta_bytes = 2 * self.n_lat * 4 + 12
+        whole_us = quant["avg_us"] + gemm["avg_us"]
+        res = {
+            "workload": DESCRIBE[name], "M": case.M, "K": case.K, "N": case.N,
+            "weight_bits": case.bits, "epilogue": case.epi,
+            "steps": steps, "warmup": warmup, "preload_s": PRELOAD_SECONDS,
+            "ms_per_step": round(ms_per_step, 5), "value": round(value, 2), "unit": "TOPS",
+            "frac_of_peak": round(value / PEAK_INT8_TOPS, 4),
+            "device": device,
+            "roofline": self.mfma_roofline(name, f"gemm_kernel<{case.bits}, bf16, {case.epi}>", L.ops,
+                                           gemm["avg_us"], 1),
+            "kernels": {
+                "quant_act": self.hbm_entry(quant_bytes, quant["avg_us"], traffic=tr.get("quant")),
+                "latent_delta": dict(self.hbm_entry(delta_bytes, delta["avg_us"], "hbm_read_gbs",
+                                                    traffic=tr.get("delta")),
+                                     note="two launches per call; the 33.5 MB of inputs stay resident in "
+                                          "the 256 MB Infinity Cache between calls (warm)"),
+                "pack_weight_offline": {"avg_launch_us": round(pack["avg_us"], 2)},
+                # quantization + GEMM + epilogue of the layer, without the latent delta
+                "qlinear_whole_call": {
+                    "achieved": round(L.ops / (whole_us * 1e-6) / 1e12, 1), "peak": PEAK_INT8_TOPS,
+                    "unit": "TOP/s", "frac": round(L.ops / (whole_us * 1e-6) / 1e12 / PEAK_INT8_TOPS, 4),
+                    "avg_us": round(whole_us, 2)},
+            },
+        }
+        if with_cold:
+            # The same two kernels on inputs that are cold in the L2s and the 256 MB Infinity
+            # Cache: each launch takes the next of enough distinct copies of its input to exceed
+            # 320 MB (a layer whose activations are larger than that is cold anyway).
+            turn = [0]
+            copies = max(2, -(-(320 << 20) // (x.numel() * 2)))
+            xs = [x] + [x.clone() for _ in range(copies - 1)]
+
+            def quant_cold():
+                self.quant_stage(L, xs[turn[0] % copies])
+                turn[0] += 1
+            qcold = batch_times_us(quant_cold, copies, max(3, 60 // copies))
+            del xs
+            pairs = -(-(320 << 20) // (2 * self.n_lat * 4))
+            lat = [(self.cur, self.prev)] + [(self.cur.clone(), self.prev.clone()) for _ in range(pairs - 1)]
+
+            def delta_cold():
+                self.delta_stage(pair=lat[turn[0] % pairs])
+                turn[0] += 1
+            dcold = batch_times_us(delta_cold, pairs, 8)
+            del lat
+            res["kernels"]["quant_act"]["cold"] = dict(
+                self.hbm_entry(quant_bytes, qcold["avg_us"]),
+                note="each launch reads the next of enough distinct input copies to exceed 320 MB")
+            cold_roof_us = self.roofs.get("read_32mib_cold_us")
+            res["kernels"]["latent_delta"]["cold"] = dict(
+                self.hbm_entry(delta_bytes, dcold["avg_us"], "hbm_read_gbs"),
+                read_only_kernel_same_bytes_us=cold_roof_us,
+                frac_of_read_only_kernel=round(cold_roof_us / dcold["avg_us"], 4) if cold_roof_us else None,
+                note="each call takes the next of enough distinct latent pairs to exceed 320 MB; "
+                     "read_only_kernel_same_bytes_us is bench/qc_roofs' single launch that only reads "
+                     "two cold 16 MiB buffers, timed the same way (launch boundary included)")
+        del L, Y, ws
+        torch.cuda.empty_cache()
+        return res, case
+
+    # -- the 28-block sweep
+    def run_sweep(self, steps, warmup):
+        torch, qc, synth = self.torch, self.qc, self.synth
+        cases = synth.stdit_block_layers()
+        M = cases[0].M
+        maxK, maxN = max(c.K for c in cases), max(c.N for c in cases)
+        ws = (qc.qlinear_asym_workspace_t if self.asym else qc.qlinear_workspace_t)(M, maxK, maxN)
+        Y = torch.empty(M * maxN, dtype=torch.bfloat16, device="cuda")
+        layers = [Layer(c, self.activations(c), ws, Y, i, self.rot, self.asym) for i, c in enumerate(cases)]
+
+        def step():
+            for L in layers:
+                self.qlinear(L)
+
+        preload(step)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        with PowerSampler() as sampler:
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+        device = sampler.summary()
+        ops = sum(L.ops for L in layers)
+        value = ops / (ms_per_step * 1e-3) / 1e12
+
+        rounds = 3
+        quant = batch_times_us(lambda: [self.quant_stage(L) for L in layers], 1, rounds)
+        gemm = batch_times_us(lambda: [self.gemm_stage(L) for L in layers], 1, rounds)
+        pack = batch_times_us(lambda: [self.pack_stage(L) for L in layers], 1, 2)
+        # the GEMM by class of layer (shape, weight bits): all layers of a class, back to back
+        by_class = {}
+        for L in layers:
+            by_class.setdefault((L.case.name.split("_")[1], L.case.bits), []).append(L)
+        classes = []
+        for (kind, bits), ls in by_class.items():
+            t = batch_times_us(lambda: [self.gemm_stage(L) for L in ls], 1, 3)
+            q = batch_times_us(lambda: [self.quant_stage(L) for L in ls], 1, 2)
+            c = ls[0].case
+            tops = sum(L.ops for L in ls) / (t["avg_us"] * 1e-6) / 1e12
+            qbytes = (c.M * c.K * 3 + 4 * c.M)
+            classes.append({"layer": kind, "K": c.K, "N": c.N, "weight_bits": bits, "layers": len(ls),
+                            "gemm_avg_launch_us": round(t["avg_us"] / len(ls), 1),
+                            "gemm_tops": round(tops, 1), "gemm_frac": round(tops / PEAK_INT8_TOPS, 4),
+                            "quant_avg_launch_us": round(q["avg_us"] / len(ls), 1),
+                            "quant_gbs": round(qbytes / (q["avg_us"] / len(ls) * 1e-6) / 1e9, 1)})
+        n = len(layers)
+        quant_bytes = sum(c.M * c.K * 3 + 4 * c.M for c in cases)
+        whole_us = quant["avg_us"] + gemm["avg_us"]
+        tr = self.traffic.get("sweep28", {}) if self.variant == "a8" else {}
+        res = {
+            "workload": DESCRIBE["sweep28"], "M": M, "layers": n,
+            "w4_layers": sum(c.bits == 4 for c in cases),
+            "steps": steps, "warmup": warmup, "preload_s": PRELOAD_SECONDS,
+            "ms_per_step": round(ms_per_step, 4), "value": round(value, 2), "unit": "TOPS",
+            "frac_of_peak": round(value / PEAK_INT8_TOPS, 4), "device": device,
+            "roofline": self.mfma_roofline("sweep28", "gemm_kernel<8|4, bf16, none|gelu_tanh> (112 launches)",
+                                           ops, gemm["avg_us"], n),
+            "kernels": {
+                "quant_act": self.hbm_entry(quant_bytes / n, quant["avg_us"] / n, traffic=tr.get("quant")),
+                "pack_weight_offline": {"avg_launch_us": round(pack["avg_us"] / n, 2)},
+                "qlinear_whole_call": {
+                    "achieved": round(ops / (whole_us * 1e-6) / 1e12, 1), "peak": PEAK_INT8_TOPS,
+                    "unit": "TOP/s", "frac": round(ops / (whole_us * 1e-6) / 1e12 / PEAK_INT8_TOPS, 4),
+                    "avg_us": round(whole_us / n, 2)},
+                "gemm_by_layer_class": classes,
+            },
+        }
+        del layers, Y, ws
+        torch.cuda.empty_cache()
+        return res, cases
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
-    # the GPU needs some tens of milliseconds of load before its clocks have ramped up; the
-    # default warm-up is ~0.1 s of steps
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=WORKLOADS, default="qkv256")
+    ap.add_argument("--workload", choices=WORKLOADS, default="sweep28",
+                    help="the headline; the default sweep also reports the single-layer "
+                         "configurations under `configs`")
     ap.add_argument("--variant", choices=tuple(VARIANTS), default="a8",
                     help="activation quantizer: a8 (default), a6 / a4 (lower bit-widths), rot128 "
                          "(Walsh-Hadamard rotation of 128-column blocks fused in), asym (zero "
                          "point per token)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="sweep28 only: skip the single-layer configurations")
+    ap.add_argument("--no-roofs", action="store_true", help="do not run bench/qc_roofs first")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 256 MiB device copies, as the reference kernel "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -202,194 +664,35 @@ def main():
               "rows without any exchange between GPUs", file=sys.stderr)
         return 2
 
-    import numpy as np
+    # the roofs first: the child process has the GPU to itself and is gone before torch starts
+    roofs = {} if args.no_roofs else measured_roofs()
+
     import torch
     from paper_2503_06545_amd import binding as qc
-    from paper_2503_06545_amd import synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     qc.lib()  # fail loudly if libqc.so is missing
 
-    def to_dev_bf16(bits):
-        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
-
-    # ---- workload ------------------------------------------------------------------------
     sweep = args.workload == "sweep28"
+    steps = args.steps if args.steps is not None else (20 if sweep else 300)
+    warmup = args.warmup if args.warmup is not None else (5 if sweep else 100)
+    bench = Bench(args.variant, roofs)
+
+    configs = {}
     if sweep:
-        cases = synth.stdit_block_layers()
-        describe = ("28 STDiT blocks x (QKV 1152->3456, out 1152->1152, fc1 1152->4608 + GELU, "
-                    "fc2 4608->1152), M = 131072 tokens (CFG batch 2 at 512x512), bf16 in/out, "
-                    "per-layer weight bit-width from the seeded mask")
-        default_steps, default_warmup = 20, 4
+        head, cases = bench.run_sweep(steps, warmup)
+        if not args.no_configs:
+            for name in SINGLE:
+                # about a quarter of a second of timed steps each, whatever --steps says
+                per_step_ms = {"qkv256": 0.075, "fc1_512": 0.37, "fc2_512_w8": 0.45, "fc2_512_w4": 0.42}[name]
+                sub_steps = max(50, int(250 / per_step_ms))
+                configs[name], _ = bench.run_single(name, sub_steps, sub_steps // 4,
+                                                    with_cold=name in ("qkv256", "fc1_512"))
     else:
-        case0 = {"qkv256": synth.QKV_256, "fc1_512": synth.FC1_512, "fc2_512_w8": synth.FC2_512_W8,
-                 "fc2_512_w4": synth.FC2_512_W4}[args.workload]
-        cases = [case0]
-        describe = {
-            "qkv256": "STDiT QKV projection 256x256, the headline configuration: X bf16 [16384,1152] "
-                      "N(0,1) with 12 outlier columns x20, W8A8 [3456,1152], bias, bf16 out",
-            "fc1_512": "STDiT MLP fc1 + GELU(tanh) 512x512: X bf16 "
-                       "[65536,1152], W8A8 [4608,1152], bf16 out",
-            "fc2_512_w8": "STDiT MLP fc2 512x512: X bf16 [65536,4608] "
-                          "post-GELU, W8A8 [1152,4608], bf16 out",
-            "fc2_512_w4": "STDiT MLP fc2 512x512: X bf16 [65536,4608] "
-                          "post-GELU, W4A8 [1152,4608] int4 weights, bf16 out",
-        }[args.workload] + "; + latent delta on 2 x [16,4,16,64,64] fp32"
-        scale = max(1, (case0.M * case0.N * case0.K) // (16384 * 3456 * 1152))
-        default_steps, default_warmup = max(200, 3000 // scale), max(100, 1000 // scale)
-    steps = args.steps if args.steps is not None else default_steps
-    warmup = args.warmup if args.warmup is not None else default_warmup
-
-    # one activation tensor per distinct (K, distribution), shared by the layers that use it
-    x_cache, layers = {}, []
-    M = cases[0].M
-    maxK = max(c.K for c in cases)
-    maxN = max(c.N for c in cases)
-    var = VARIANTS[args.variant]
-    act_bits, rot, asym = var["act_bits"], var.get("rot", 0), var.get("asym", False)
-    ws = (qc.qlinear_asym_workspace_t if asym else qc.qlinear_workspace_t)(M, maxK, maxN)
-    Y = torch.empty(M * maxN, dtype=torch.bfloat16, device="cuda")
-    for i, c in enumerate(cases):
-        key = (c.K, c.post_gelu, c.outliers)
-        if key not in x_cache:
-            x_cache[key] = to_dev_bf16(c.x())
-        layers.append(Layer(c, x_cache[key], ws, Y, layer_index=i, rot=rot, asym=asym))
-    w4_layers = sum(c.bits == 4 for c in cases)
-
-    cur_h, prev_h = synth.latent_pair(seed=0)
-    cur, prev = torch.from_numpy(cur_h).cuda(), torch.from_numpy(prev_h).cuda()
-    n_lat = cur.numel()
-    dws = qc.latent_delta_workspace_t(n_lat)
-    out3 = torch.empty(3, dtype=torch.float32, device="cuda")
-    stream = torch.cuda.current_stream().cuda_stream
-    # The latent change does not depend on the linear: the step issues it on a second stream
-    # (default priority) so that this HBM-bound reduction runs beside the GEMM.  Successive
-    # calls on that stream share one workspace and are ordered by the stream itself.
-    side = torch.cuda.Stream()
-    side_stream = side.cuda_stream
-
-    def check(st):
-        if st != qc.QC_OK:
-            raise qc.QcError(st, "bench step")
-
-    def qlinear(L):
-        c = L.case
-        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16,
-                L.ws.data_ptr(), L.ws.numel(), stream)
-        head = (L.x.data_ptr(), qc.QC_BF16, c.M, c.K)
-        if asym:
-            check(qc.qc_qlinear_asym(*head, act_bits, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
-                                     L.row_sums.data_ptr(), *tail))
-        elif rot:
-            check(qc.qc_qlinear_rot(*head, act_bits, rot, L.pw.blob.data_ptr(),
-                                    L.pw.scale.data_ptr(), *tail))
-        elif act_bits != 8:
-            check(qc.qc_qlinear_act_bits(*head, act_bits, L.pw.blob.data_ptr(),
-                                         L.pw.scale.data_ptr(), *tail))
-        else:
-            check(qc.qc_qlinear(*head, L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
-
-    def quant_stage(L):
-        c = L.case
-        head = (L.x.data_ptr(), qc.QC_BF16, c.M, c.K)
-        tail = (L.ws.data_ptr(), L.ws.numel(), stream)
-        if asym:
-            check(qc.qc_qlinear_asym_quant(*head, act_bits, *tail))
-        elif rot:
-            check(qc.qc_qlinear_quant_rot(*head, act_bits, rot, *tail))
-        else:
-            check(qc.qc_qlinear_quant_bits(*head, act_bits, *tail))
-
-    def gemm_stage(L):
-        c = L.case
-        tail = (c.bits, c.N, L.bias.data_ptr(), L.epi, L.Y.data_ptr(), qc.QC_OUT_BF16, stream)
-        if asym:
-            check(qc.qc_qlinear_asym_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
-                                          L.pw.blob.data_ptr(), L.pw.scale.data_ptr(),
-                                          L.row_sums.data_ptr(), *tail))
-        else:
-            check(qc.qc_qlinear_gemm(L.ws.data_ptr(), L.ws.numel(), c.M, c.K,
-                                     L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), *tail))
-
-    def delta_stage(on=None):
-        check(qc.qc_latent_delta(cur.data_ptr(), prev.data_ptr(), n_lat, out3.data_ptr(),
-                                 dws.data_ptr(), dws.numel(), stream if on is None else on))
-
-    def pack_stage(L):
-        c = L.case
-        if rot:
-            check(qc.qc_pack_weight_rot(L.W.data_ptr(), c.N, c.K, c.bits, rot,
-                                        L.pw.blob.data_ptr(), L.pw.scale.data_ptr(), stream))
-        else:
-            check(qc.qc_pack_weight(L.W.data_ptr(), c.N, c.K, c.bits, L.pw.blob.data_ptr(),
-                                    L.pw.scale.data_ptr(), stream))
-
-    def step():
-        for L in layers:
-            qlinear(L)
-        if not sweep:
-            delta_stage(side_stream)
-
-    # ---- headline: K steps between two full synchronisations ----------------------------
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    with PowerSampler() as sampler:
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    device_info = dict(name=torch.cuda.get_device_name(0), **sampler.summary())
-    ops = sum(L.ops for L in layers)
-    value = ops / (ms_per_step * 1e-3) / 1e12
-
-    # ---- per-kernel durations --------------------------------------------------------------
-    if sweep:
-        batch, rounds = 1, 3
-    else:
-        batch = 20
-        rounds = max(3, min(steps, 600) // batch)
-    for _ in range(min(warmup, 300)):
-        step()
-    per = {
-        "quant": batch_times_us(lambda: [quant_stage(L) for L in layers], batch, rounds),
-        "gemm": batch_times_us(lambda: [gemm_stage(L) for L in layers], batch, rounds),
-        "pack": batch_times_us(lambda: [pack_stage(L) for L in layers], 1, 5),
-    }
-    if not sweep:
-        per["delta"] = batch_times_us(delta_stage, batch, rounds)
-        # The same two kernels on inputs that are cold in the L2s and the 256 MB Infinity Cache:
-        # each launch takes the next of enough distinct copies of its input to exceed 320 MB
-        # (a layer whose activations are larger than that is cold anyway).
-        L0 = layers[0]
-        copies = max(2, -(-(320 << 20) // (L0.x.numel() * 2)))
-        xs = [L0.x] + [L0.x.clone() for _ in range(copies - 1)]
-        turn = [0]
-
-        def quant_cold():
-            x = xs[turn[0] % copies]
-            turn[0] += 1
-            check(qc.qc_qlinear_quant_bits(x.data_ptr(), qc.QC_BF16, L0.case.M, L0.case.K, act_bits,
-                                           L0.ws.data_ptr(), L0.ws.numel(), stream)
-                  if not (asym or rot) else
-                  (qc.qc_qlinear_asym_quant(x.data_ptr(), qc.QC_BF16, L0.case.M, L0.case.K, act_bits,
-                                            L0.ws.data_ptr(), L0.ws.numel(), stream) if asym else
-                   qc.qc_qlinear_quant_rot(x.data_ptr(), qc.QC_BF16, L0.case.M, L0.case.K, act_bits,
-                                           rot, L0.ws.data_ptr(), L0.ws.numel(), stream)))
-        per["quant_cold"] = batch_times_us(quant_cold, copies, max(3, 60 // copies))
-        pairs = -(-(320 << 20) // (2 * n_lat * 4))
-        lat = [(cur, prev)] + [(cur.clone(), prev.clone()) for _ in range(pairs - 1)]
-
-        def delta_cold():
-            a, b = lat[turn[0] % pairs]
-            turn[0] += 1
-            check(qc.qc_latent_delta(a.data_ptr(), b.data_ptr(), n_lat, out3.data_ptr(),
-                                     dws.data_ptr(), dws.numel(), stream))
-        per["delta_cold"] = batch_times_us(delta_cold, pairs, 6)
-        del xs, lat
+        head, case = bench.run_single(args.workload, steps, warmup)
+        cases = [case]
 
     if args.calibration_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -398,82 +701,44 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}) if args.variant == "a8" else {}
-    gemm_us = per["gemm"]["avg_us"]
-    gemm_tops = ops / (gemm_us * 1e-6) / 1e12
-    quant_bytes = sum(c.M * c.K * 3 + 4 * c.M for c in cases)
-    quant_gbs = quant_bytes / (per["quant"]["avg_us"] * 1e-6) / 1e9
-    kernel_name = ("gemm_kernel<8|4, bf16, none|gelu_tanh> (112 launches)" if sweep else
-                   f"gemm_kernel<{cases[0].bits}, bf16, {cases[0].epi}>")
-
     result = {
         "metric": "quantized-linear int8 TOPS, whole qc_qlinear" +
                   ("" if sweep else " + qc_latent_delta") + " step, 1 MI355X",
-        "value": round(value, 2),
+        "value": head["value"],
         "unit": "TOPS",
         "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; bf16 in/out, fp32 scales)",
         "data": "synthetic",
-        "config": {"workload": describe, "name": args.workload, "variant": args.variant,
-                   "activation_quantizer": {"a8": "symmetric int8 per token", "a6": "symmetric 6 bit per token",
-                                            "a4": "symmetric 4 bit per token",
-                                            "rot128": "Walsh-Hadamard blocks of 128 columns, then symmetric int8 per token",
-                                            "asym": "asymmetric uint8 per token with zero point"}[args.variant],
-                   "layers": len(cases),
-                   "w4_layers": w4_layers, "M": M, "seed": cases[0].seed,
+        "config": {"workload": head["workload"], "name": args.workload, "variant": args.variant,
+                   "activation_quantizer": VARIANT_TEXT[args.variant],
+                   "layers": len(cases), "w4_layers": sum(c.bits == 4 for c in cases),
+                   "M": cases[0].M, "seed": cases[0].seed,
+                   "preload_s": PRELOAD_SECONDS,
                    "offline_not_in_step": "qc_pack_weight",
                    "streams": "qc_qlinear on the current stream" +
                               ("" if sweep else ", qc_latent_delta on a second one")},
-        "device": device_info,
-        "roofline": {"bound": "mfma", "kernel": kernel_name,
-                     "achieved": round(gemm_tops, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4),
-                     "traffic": traffic.get("gemm"),
-                     "ops_per_launch": ops / len(cases), "launches_per_step": len(cases),
-                     "avg_launch_us": round(gemm_us / len(cases), 2)},
-        "kernels": {
-            "quant_act": {"bound": "hbm", "achieved": round(quant_gbs, 1), "peak": PEAK_HBM_GBS,
-                          "unit": "GB/s", "frac": round(quant_gbs / PEAK_HBM_GBS, 4),
-                          "bytes_per_launch": quant_bytes / len(cases),
-                          "avg_launch_us": round(per["quant"]["avg_us"] / len(cases), 2),
-                          "traffic": traffic.get("quant")},
-            "pack_weight_offline": {"avg_launch_us": round(per["pack"]["avg_us"] / len(cases), 2)},
-            # quantization + GEMM + epilogue of the layer(s), without the latent delta
-            "qlinear_whole_call": {
-                "achieved": round(ops / ((per["quant"]["avg_us"] + gemm_us) * 1e-6) / 1e12, 1),
-                "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": round(ops / ((per["quant"]["avg_us"] + gemm_us) * 1e-6) / 1e12 / PEAK_INT8_TOPS, 4),
-                "avg_us": round((per["quant"]["avg_us"] + gemm_us) / len(cases), 2)},
-        },
+        "device": dict(name=torch.cuda.get_device_name(0), **head["device"]),
+        "roofline": head["roofline"],
+        "kernels": head["kernels"],
+        "achievable_roofs": roofs,
+        "provenance": provenance(),
     }
     if not sweep:
         c = cases[0]
         result["config"].update({"K": c.K, "N": c.N, "weight_bits": c.bits, "epilogue": c.epi})
-        delta_bytes = 2 * n_lat * 4 + 12
-        delta_gbs = delta_bytes / (per["delta"]["avg_us"] * 1e-6) / 1e9
-        result["kernels"]["latent_delta"] = {
-            "bound": "hbm", "achieved": round(delta_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": round(delta_gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": delta_bytes,
-            "avg_launch_us": round(per["delta"]["avg_us"], 2),
-            "note": "two launches per call; the 33.5 MB of inputs stay resident in the 256 MB "
-                    "Infinity Cache between calls (warm)",
-            "traffic": traffic.get("delta"),
-            "cold": {"avg_launch_us": round(per["delta_cold"]["avg_us"], 2),
-                     "achieved": round(delta_bytes / (per["delta_cold"]["avg_us"] * 1e-6) / 1e9, 1),
-                     "frac": round(delta_bytes / (per["delta_cold"]["avg_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}}
-        qc_us = per["quant_cold"]["avg_us"]
-        result["kernels"]["quant_act"]["cold"] = {
-            "avg_launch_us": round(qc_us, 2), "achieved": round(quant_bytes / (qc_us * 1e-6) / 1e9, 1),
-            "frac": round(quant_bytes / (qc_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
-            "note": "each launch reads the next of enough distinct input copies to exceed 320 MB"}
+    if configs:
+        result["configs"] = configs
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cases[0], act_bits, rot, asym)
+        if sweep:
+            result["cpu_baseline"] = cpu_baseline_sweep(cases, bench.act_bits, bench.rot, bench.asym)
+        else:
+            result["cpu_baseline"] = cpu_baseline_layer(cases[0], bench.act_bits, bench.rot, bench.asym)
     print(json.dumps(result))
     return 0
 

@@ -2,13 +2,16 @@
 // libqc are judged: streaming HBM bandwidth, the int8 MFMA issue rate with all-zero and with
 // random operands (the chip is power limited: the clock it holds depends on how many bits
 // toggle), the same MFMA loop fed with operand traffic in the proportions of the GEMM kernel,
-// and LDS / L2 delivery rates per CU.  Stand-alone program, no arguments; prints one line per
-// measurement.  Each measurement runs for several tens of milliseconds so that the clocks
-// have settled.
+// and LDS / L2 delivery rates per CU.  Stand-alone program, not part of libqc; prints one line
+// per measurement, each followed by a machine-readable "@key value" line that bench.py reads.
+// `--quick` runs only the measurements bench.py puts beside its own numbers (HBM streams, the
+// cold 32 MiB read, the 16x16x64 MFMA loop).  Each measurement runs for several tens of
+// milliseconds so that the clocks have settled.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include <type_traits>
 #include <vector>
@@ -26,20 +29,63 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ---- HBM ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ a,
-                                                   float4 *__restrict__ b, int64_t n4) {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) b[i] = a[i];
+// Copy: like the read stream below, U loads of a lane in flight, then its U stores.
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void copy_kernel(const float4 *__restrict__ a,
+                                                       float4 *__restrict__ b, int64_t n4) {
+    constexpr int64_t kChunk = (int64_t)THREADS * U;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4; base += (int64_t)gridDim.x * kChunk) {
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            v[u] = a[i < n4 ? i : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            if (i < n4) b[i] = v[u];
+        }
+    }
 }
 
-__global__ __launch_bounds__(256) void read_kernel(const float4 *__restrict__ a, float *out,
-                                                   int64_t n4) {
-    const int64_t stride = (int64_t)gridDim.x * 256;
+// Read-only stream: a block takes contiguous chunks of THREADS * U float4 and strides over the
+// buffer by the grid; the U loads of a lane are all in flight before the first use.
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void read_kernel(const float4 *__restrict__ a, float *out,
+                                                       int64_t n4) {
     float s = 0;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n4; i += 4 * stride) {
-        const float4 v0 = a[i], v1 = a[i + stride], v2 = a[i + 2 * stride], v3 = a[i + 3 * stride];
-        s += v0.x + v1.y + v2.z + v3.w;
+    constexpr int64_t kChunk = (int64_t)THREADS * U;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4; base += (int64_t)gridDim.x * kChunk) {
+        float4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            v[u] = a[i < n4 ? i : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) s += v[u].x + v[u].w;
+    }
+    if (s == 12345.678f) out[0] = s;
+}
+
+// The same over two buffers at once (the access pattern of the latent-change reduction).
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void read2_kernel(const float4 *__restrict__ a,
+                                                        const float4 *__restrict__ b, float *out,
+                                                        int64_t n4) {
+    float s = 0;
+    constexpr int64_t kChunk = (int64_t)THREADS * U;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4; base += (int64_t)gridDim.x * kChunk) {
+        float4 v[U], w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            v[u] = a[i < n4 ? i : 0];
+            w[u] = b[i < n4 ? i : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) s += v[u].x + w[u].w;
     }
     if (s == 12345.678f) out[0] = s;
 }
@@ -203,7 +249,8 @@ static float settled_ms(F launch) {
     return sum / 3;
 }
 
-int main() {
+int main(int argc, char **argv) {
+    const bool quick = argc > 1 && strcmp(argv[1], "--quick") == 0;
     hipDeviceProp_t prop;
     CK(hipGetDeviceProperties(&prop, 0));
     const int CU = prop.multiProcessorCount;
@@ -220,10 +267,51 @@ int main() {
         CK(hipMalloc(&b, n));
         CK(hipMemset(a, 1, n));
         CK(hipMemset(b, 2, n));
-        float ms = settled_ms([&] { read_kernel<<<16384, 256>>>(a, (float *)dout, n / 16); });
-        printf("hbm  read-only stream, 1 GiB:            %7.0f GB/s\n", n / ms * 1e-6);
-        ms = settled_ms([&] { copy_kernel<<<65536, 256>>>(a, b, n / 16); });
-        printf("hbm  copy, 1 GiB read + 1 GiB written:   %7.0f GB/s\n", 2.0 * n / ms * 1e-6);
+        float ms = settled_ms([&] { read_kernel<256, 4><<<16384, 256>>>(a, (float *)dout, n / 16); });
+        float ms2 = settled_ms([&] { read_kernel<1024, 4><<<CU, 1024>>>(a, (float *)dout, n / 16); });
+        float ms3 = settled_ms([&] { read_kernel<256, 8><<<8 * CU, 256>>>(a, (float *)dout, n / 16); });
+        const float best = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
+        printf("hbm  read-only stream, 1 GiB (best of three launch shapes: %.0f / %.0f / %.0f): %7.0f GB/s\n",
+               n / ms * 1e-6, n / ms2 * 1e-6, n / ms3 * 1e-6, n / best * 1e-6);
+        printf("@hbm_read_gbs %.0f\n", n / best * 1e-6);
+        ms = settled_ms([&] { copy_kernel<256, 1><<<65536, 256>>>(a, b, n / 16); });
+        ms2 = settled_ms([&] { copy_kernel<256, 4><<<8 * CU, 256>>>(a, b, n / 16); });
+        ms3 = settled_ms([&] { copy_kernel<1024, 4><<<CU, 1024>>>(a, b, n / 16); });
+        const float cbest = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
+        printf("hbm  copy, 1 GiB read + 1 GiB written (best of three launch shapes: %.0f / %.0f / %.0f): %7.0f GB/s\n",
+               2.0 * n / ms * 1e-6, 2.0 * n / ms2 * 1e-6, 2.0 * n / ms3 * 1e-6, 2.0 * n / cbest * 1e-6);
+        printf("@hbm_copy_gbs %.0f\n", 2.0 * n / cbest * 1e-6);
+        // Two 16 MiB buffers per launch (the size of the latent pair), each launch on the next
+        // of 12 distinct pairs so that nothing is left in the caches from the launch before, and
+        // the same on one pair that stays in the Infinity Cache.  Timed as bench.py times its
+        // kernels: events around a batch of back-to-back launches, so the figure includes what
+        // a launch boundary costs.
+        const int64_t m = (int64_t)16 << 20;   // bytes per buffer
+        hipEvent_t e0, e1;
+        CK(hipEventCreate(&e0));
+        CK(hipEventCreate(&e1));
+        for (int cold = 1; cold >= 0; --cold) {
+            float sum = 0;
+            const int rounds = 10, batch = 24;
+            for (int r = -300; r < rounds; ++r) {   // about 50 ms of the same launches first
+                CK(hipEventRecord(e0));
+                for (int i = 0; i < batch; ++i) {
+                    const int64_t off = cold ? (int64_t)(i % 12) * 2 * m : 0;
+                    read2_kernel<1024, 4><<<CU, 1024>>>((const float4 *)((const char *)a + off),
+                                                        (const float4 *)((const char *)a + off + m),
+                                                        (float *)dout, m / 16);
+                }
+                CK(hipEventRecord(e1));
+                CK(hipEventSynchronize(e1));
+                float t;
+                CK(hipEventElapsedTime(&t, e0, e1));
+                if (r >= 0) sum += t / batch;
+            }
+            const double us = sum / rounds * 1e3;
+            printf("hbm  read-only, 2 x 16 MiB per launch, %s: %6.2f us per launch, %7.0f GB/s\n",
+                   cold ? "cold (12 pairs in turn)" : "warm (one pair, cache resident)", us, 2.0 * m / us * 1e-3);
+            printf("@read_32mib_%s_us %.2f\n", cold ? "cold" : "warm", us);
+        }
         CK(hipFree(a));
         CK(hipFree(b));
     }
@@ -254,25 +342,33 @@ int main() {
     const double ops = (double)blocks * 4 * iters * 16 * 65536.0;
     auto tops = [&](float ms) { return ops / ms * 1e-9; };
     // Operand traffic is quoted per 32 K multiply-adds: one 32x32x32 or two 16x16x64 operations.
-    auto mfma_lines = [&](auto m16_tag, const char *form) {
+    auto mfma_lines = [&](auto m16_tag, const char *form, const char *key) {
         constexpr bool M16 = decltype(m16_tag)::value;
-        printf("mfma %s, 2 wavefronts/SIMD, registers only, zero operands:  %5.0f TOPS\n", form,
-               tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_zero, gsrc, iters, dout); })));
-        printf("  random int8 operands:                                                 %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-        printf("  random + 0.5 ds_read_b128 per 32 K multiply-adds:                     %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<8, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-        printf("  random + 256 B loaded from L2:                                        %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<0, 4, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-        printf("  random + 256 B copied L2 -> LDS and read back from LDS:               %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<0, 4, true, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-        printf("  random + 0.5 ds_read_b128 and 384 B from L2 (the GEMM's proportions): %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<8, 6, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
-        printf("  random + 0.5 ds_read_b128 and 128 B from L2:                          %5.0f TOPS\n",
-               tops(settled_ms([&] { mfma_kernel<8, 2, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        double v;
+        v = tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_zero, gsrc, iters, dout); }));
+        printf("mfma %s, 2 wavefronts/SIMD, registers only, zero operands:  %5.0f TOPS\n", form, v);
+        printf("@mfma_%s_zero_tops %.0f\n", key, v);
+        v = tops(settled_ms([&] { mfma_kernel<0, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); }));
+        printf("  random int8 operands:                                                 %5.0f TOPS\n", v);
+        printf("@mfma_%s_random_tops %.0f\n", key, v);
+        if (!quick) {
+            printf("  random + 0.5 ds_read_b128 per 32 K multiply-adds:                     %5.0f TOPS\n",
+                   tops(settled_ms([&] { mfma_kernel<8, 0, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+            printf("  random + 256 B loaded from L2:                                        %5.0f TOPS\n",
+                   tops(settled_ms([&] { mfma_kernel<0, 4, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+            printf("  random + 256 B copied L2 -> LDS and read back from LDS:               %5.0f TOPS\n",
+                   tops(settled_ms([&] { mfma_kernel<0, 4, true, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
+        }
+        v = tops(settled_ms([&] { mfma_kernel<8, 6, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); }));
+        printf("  random + 0.5 ds_read_b128 and 384 B from L2 (the GEMM's proportions): %5.0f TOPS\n", v);
+        printf("@mfma_%s_gemm_traffic_tops %.0f\n", key, v);
+        if (!quick)
+            printf("  random + 0.5 ds_read_b128 and 128 B from L2:                          %5.0f TOPS\n",
+                   tops(settled_ms([&] { mfma_kernel<8, 2, false, M16><<<blocks, 256>>>(d_rand, gsrc, iters, dout); })));
     };
-    mfma_lines(std::false_type{}, "v_mfma_i32_32x32x32_i8");
-    mfma_lines(std::true_type{}, "v_mfma_i32_16x16x64_i8");
+    if (!quick) mfma_lines(std::false_type{}, "v_mfma_i32_32x32x32_i8", "32x32x32");
+    mfma_lines(std::true_type{}, "v_mfma_i32_16x16x64_i8", "16x16x64");
+    if (quick) return 0;
 
     {
         const int li = 20000;

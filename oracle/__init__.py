@@ -45,7 +45,10 @@ EPI_NONE, EPI_GELU_TANH, EPI_GELU_ERF = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
-    """Compile qc_oracle.c with gcc (-O2, no contraction, OpenMP over rows)."""
+    """Compile qc_oracle.c with gcc (-O2, no contraction, OpenMP over rows).  QC_ORACLE_LIB names
+    a differently compiled copy of the same source to load instead (the sanitizer test's)."""
+    if os.environ.get("QC_ORACLE_LIB"):
+        return os.environ["QC_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall",
                "-Wextra", _SRC, "-o", _LIB, "-lm"]

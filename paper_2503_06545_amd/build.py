@@ -7,6 +7,7 @@ operand registers are never spilled, so a kernel that needs scratch memory fails
 """
 from __future__ import annotations
 
+import json
 import os
 import re
 import subprocess
@@ -89,6 +90,12 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("kernels that use scratch memory (register spills), or no resource "
                            f"report at all: {spilled}")
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], check=True)
+    # which sources the library was built from: the tree travels to the GPU machine without its
+    # history, so the benchmark reads the commit from this stamp
+    git = subprocess.run(["git", "-C", ROOT, "describe", "--always", "--dirty", "--abbrev=12"],
+                         capture_output=True, text=True)
+    with open(os.path.join(OBJ_DIR, "build_info.json"), "w") as f:
+        json.dump({"git": git.stdout.strip() or None}, f)
     if verbose:
         print(f"built {LIB} ({len(kernels)} kernels, none uses scratch memory)", file=sys.stderr)
     return LIB

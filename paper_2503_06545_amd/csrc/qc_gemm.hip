@@ -35,7 +35,7 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
-constexpr int kStages = 3;   // LDS ring of weight stages
+constexpr int kStages = 3;   // LDS ring of weight stages (4 and 6 were measured: 1.5 % and 3 % slower)
 constexpr int kXSlots = 3;   // register ring of activation stages
 
 template <int BITS>
@@ -78,7 +78,21 @@ __device__ inline float gelu_tanh_f(float y) {
     return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
-__device__ inline float gelu_erf_f(float y) { return 0.5f * y * (1.0f + erff(y * 0.70710678118654752f)); }
+// 0.5 y (1 + erf(y / sqrt 2)) with erfc(x) = t (a1 + t (a2 + .. a5 t)) exp(-x^2), t = 1 / (1 + p x)
+// for x >= 0 (Abramowitz and Stegun 7.1.26, absolute error below 1.5e-7) and erf odd.  For
+// negative y the product form keeps the small result's relative accuracy.  Far fewer registers
+// than the math library's erff, which matters next to 128 live accumulators.
+__device__ inline float gelu_erf_f(float y) {
+    const float x = fabsf(y) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float q = p * t * __builtin_amdgcn_exp2f(x * x * -1.4426950408889634f);  // erfc(x)
+    const float gate = y >= 0.0f ? 2.0f - q : q;
+    return 0.5f * y * gate;
+}
 
 // two floats -> two bf16 (round to nearest even), one v_cvt_pk_bf16_f32
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
@@ -103,8 +117,8 @@ __device__ inline void tile_of_block(int b, int nblocks, int m_tiles, int n_tile
     nt = r / gm;
 }
 
-// vmcnt(n) with the other counters left unconstrained (gfx9 encoding, n < 16)
-#define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
+// vmcnt(n) with the other counters left unconstrained (gfx9 encoding: bits 3:0 and 15:14, n < 64)
+#define QC_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 
 // ASYM: the activation codes are the unsigned codes of the asymmetric quantizer minus a shift h
 // (128 for 8-bit codes, else 0; Section 3.1 Eq. (3)-(4) as printed).  With c[m] = h - z[m] the dequantized activation
@@ -222,13 +236,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 
     // One 64-k stage.  SLOT = stage % 3 and NEXT2 = (stage + 2) % 3 are literal constants (the
     // loop is unrolled by three) so the activation ring stays in fixed registers.
-    // VMEM operations complete in issue order; the issue order per wavefront is
-    //   W(0) X(0) W(1) X(1) W(2), then in stage s: X(s+2), W(s+3)
-    // X(s+2) goes out after the wait for X(s), among the first MFMAs of the stage, so at that
-    // wait W(s+1) X(s+1) W(s+2) are behind X(s) (2 FPW + 4 operations), and at the wait for
-    // W(s+1) in the middle of the stage X(s+1) W(s+2) X(s+2) are behind it (FPW + 8).  Past the end of K the stage index is
-    // clamped to the last stage: those copies repeat data that is not used again (they hit
-    // in cache), which keeps the instruction stream and the wait counts uniform.
+    // VMEM operations complete in issue order; with D = kStages the issue order per wavefront is
+    //   W(0) .. W(D-3) X(0) W(D-2) X(1) W(D-1), then in stage s: X(s+2), W(s+D)
+    // i.e. from X(0) on an X and a W alternate.  X(s+2) goes out after the wait for X(s), among
+    // the first MFMAs of the stage, so at that wait W X(s+1) W are behind X(s) (2 FPW + 4
+    // operations).  At the wait for W(s+1) in the middle of the stage, D - 1 activation stages
+    // and D - 2 weight stages are behind it, once the stage is past the first D - 3, whose
+    // weights are waited for before the loop.  (A deeper weight ring buys nothing: the loop is
+    // not waiting for the weights.)  Past the end
+    // of K the stage index is clamped to the last stage: those copies repeat data that is not
+    // used again (they hit in cache), which keeps the instruction stream and the wait counts
+    // uniform.
+    constexpr int kWBehind = 4 * (kStages - 1) + FPW * (kStages - 2);
+    static_assert(kStages >= 3 && kWBehind < 64, "vmcnt is a 6-bit counter");
     const int last = stages - 1;
 #define QC_CLAMP(st) ((st) < last ? (st) : last)
     // The sixteen MFMAs of a half stage (4 token blocks x 4 channel blocks) are independent, so
@@ -250,13 +270,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                 acc[i][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(                             \
                     xq[SLOT][i], BITS == 8 ? wr[0][t] : w4a[t], acc[i][t], 0, 0, 0);           \
         __builtin_amdgcn_sched_barrier(0);                                                     \
-        QC_WAIT_VMCNT(FPW + 8);                                         /* W(s+1) has landed */\
+        QC_WAIT_VMCNT(kWBehind);                                        /* W(s+1) has landed */\
         /* this wavefront's reads of W(s) are done ... */                                      \
         if (BITS == 8) QC_WAIT_W(0, 1);                                                        \
         __builtin_amdgcn_s_barrier(); /* ... and everybody else's: ring buffer s % 3 is free */\
         asm volatile("" ::: "memory");                                                         \
         if (BITS == 4) unpack(w4b, 1);   /* before the reads below overwrite the nibbles */     \
-        issue_w(QC_CLAMP((s) + 3), (s) + 3);                                                   \
+        issue_w(QC_CLAMP((s) + kStages), (s) + kStages);                                       \
         /* after the last stage this reads data that is not used */                            \
         QC_READ_W((s) + 1, 0);                                                                 \
         QC_MFMA_LOOPS                                                                          \
@@ -266,12 +286,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     } while (0)
 
     // ---- main loop -------------------------------------------------------------------
-    issue_w(0, 0);
+#pragma unroll
+    for (int j = 0; j < kStages - 2; ++j) issue_w(QC_CLAMP(j), j);
     QC_ISSUE_X(0, 0);
-    issue_w(QC_CLAMP(1), 1);
+    issue_w(QC_CLAMP(kStages - 2), kStages - 2);
     QC_ISSUE_X(QC_CLAMP(1), 1);
-    issue_w(QC_CLAMP(2), 2);
-    QC_WAIT_VMCNT(8 + 2 * FPW);   // W(0) has landed: behind it are X(0) W(1) X(1) W(2)
+    issue_w(QC_CLAMP(kStages - 1), kStages - 1);
+    // W(0) .. W(kStages - 3) have landed: behind them are X(0) W X(1) W
+    QC_WAIT_VMCNT(8 + 2 * FPW);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     QC_READ_W(0, 0);

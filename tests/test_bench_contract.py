@@ -15,29 +15,77 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
 
 
-@pytest.mark.gpu
-@pytest.mark.parametrize("extra", [[], ["--variant", "asym"]])
-def test_one_json_line_with_the_contract_keys(extra):
-    r = subprocess.run([sys.executable, BENCH, "--steps", "20", "--warmup", "20"] + extra,
-                       capture_output=True, text=True, timeout=600)
+CONTRACT_KEYS = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
+                 "higher_is_better", "scaling", "vs_baseline", "dtype", "data", "config",
+                 "roofline", "cpu_baseline")
+
+
+def run_bench(extra):
+    r = subprocess.run([sys.executable, BENCH] + extra, capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
     d = json.loads(lines[0])
-    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
-                "higher_is_better", "scaling", "vs_baseline", "dtype", "data", "config",
-                "roofline", "cpu_baseline"):
+    for key in CONTRACT_KEYS:
         assert key in d, key
-    assert d["n_gpus"] == 1 and d["steps"] == 20 and d["warmup"] == 20 and d["data"] == "synthetic"
+    assert d["n_gpus"] == 1 and d["data"] == "synthetic"
     assert d["vs_baseline"] is None and d["higher_is_better"] is True
     assert "workload" in d["config"] and "model" not in d["config"]
-    rf = d["roofline"]
+    return d
+
+
+def check_roofline(rf):
     assert rf["bound"] == "mfma" and rf["unit"] == "TOP/s" and rf["peak"] == 5000.0
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3 and 0.05 < rf["frac"] < 1.0
+    ach = rf["achievable"]
+    assert 1000 < ach["mfma_with_the_gemms_operand_traffic"] < ach["mfma_registers_only_random_operands"] <= 5100
+    assert abs(rf["frac_of_achievable"] - rf["achieved"] / ach["mfma_registers_only_random_operands"]) < 1e-3
+
+
+@pytest.mark.gpu
+def test_default_run_is_the_sweep_with_the_single_layer_configurations():
+    """The command the round's end runs (with fewer steps): headline = the 28-block sweep."""
+    d = run_bench(["--gpus", "1", "--steps", "3", "--warmup", "1"])
+    assert d["steps"] == 3 and d["warmup"] == 1
+    assert d["config"]["name"] == "sweep28" and "M = 131072" in d["config"]["workload"]
+    assert d["config"]["layers"] == 112 and 20 <= d["config"]["w4_layers"] <= 50
+    ops = sum(2.0 * 131072 * n * k for n, k in ((3456, 1152), (1152, 1152), (4608, 1152), (1152, 4608))) * 28
+    assert abs(d["value"] - ops / (d["ms_per_step"] * 1e-3) / 1e12) < 0.01 * d["value"]
+    check_roofline(d["roofline"])
+    assert d["roofline"]["launches_per_step"] == 112
+    assert d["device"]["samples"] > 10           # the timed region is long enough to sample
+    roofs = d["achievable_roofs"]
+    assert 3000 < roofs["hbm_read_gbs"] < 8000 and 3000 < roofs["hbm_copy_gbs"] < 8000
+    assert roofs["read_32mib_cold_us"] > roofs["read_32mib_warm_us"] > 1.0
+    assert len(d["provenance"]["source_sha16"]) == 16 and d["provenance"]["rocm"]
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
+    assert d["value"] > 100 * cb["value"] and len(cb["classes"]) == 8
+    k = d["kernels"]
+    assert k["qlinear_whole_call"]["achieved"] < d["roofline"]["achieved"]
+    assert {c["layer"] for c in k["gemm_by_layer_class"]} == {"qkv", "out", "fc1", "fc2"}
+    assert set(d["configs"]) == {"qkv256", "fc1_512", "fc2_512_w8", "fc2_512_w4"}
+    for name, c in d["configs"].items():
+        check_roofline(c["roofline"])
+        assert abs(c["value"] - 2.0 * c["M"] * c["N"] * c["K"] / (c["ms_per_step"] * 1e-3) / 1e12) < 0.01 * c["value"]
+        assert c["kernels"]["quant_act"]["frac"] > 0.2 and c["kernels"]["latent_delta"]["avg_launch_us"] > 0
+        assert c["kernels"]["qlinear_whole_call"]["achieved"] < c["roofline"]["achieved"]
+        assert c["device"]["samples"] > 10
+    for name in ("qkv256", "fc1_512"):
+        k = d["configs"][name]["kernels"]
+        assert k["quant_act"]["cold"]["avg_launch_us"] > 0 and k["latent_delta"]["cold"]["avg_launch_us"] > 0
+        assert 0.3 < k["latent_delta"]["cold"]["frac_of_read_only_kernel"] <= 1.05
+
+
+@pytest.mark.gpu
+def test_single_layer_headline_with_another_activation_quantizer():
+    d = run_bench(["--workload", "qkv256", "--variant", "asym", "--steps", "20", "--warmup", "20"])
+    assert d["steps"] == 20 and d["warmup"] == 20 and "configs" not in d
+    check_roofline(d["roofline"])
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
     assert d["value"] > 100 * cb["value"] and 0 < cb["one_thread"]["value"] <= cb["value"]
     k = d["kernels"]
     assert k["quant_act"]["cold"]["avg_launch_us"] > 0 and k["latent_delta"]["cold"]["avg_launch_us"] > 0
-    assert k["qlinear_whole_call"]["achieved"] < rf["achieved"]
+    assert k["qlinear_whole_call"]["achieved"] < d["roofline"]["achieved"]
     assert abs(d["value"] - 2.0 * 16384 * 3456 * 1152 / (d["ms_per_step"] * 1e-3) / 1e12) < 0.01 * d["value"]

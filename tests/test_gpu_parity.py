@@ -205,6 +205,51 @@ def test_qlinear_ragged_shapes(bits, M, K, N):
     run_linear_case(synth.to_bf16_bits(x), W, None, bits, "gelu_tanh", "bf16", check_acc=False)
 
 
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("epi", ["gelu_tanh", "gelu_erf"])
+def test_gelu_dense_sweep_through_the_epilogue(epi, out):
+    """All-zero activations give zero accumulators, so Y[m, n] = act(bias[n]): the bias sweeps
+    the activation's argument densely over [-8, 8] (and far outside), every output against the
+    oracle's fp64 formula rounded once.  Bars: the output tolerances with the RMS term replaced
+    by 1 (the scale of an fc1 output), i.e. an absolute 1e-3 / 2e-2 near zero."""
+    N, K, M = 16384 + 8, 64, 16
+    b = np.concatenate([np.linspace(-8.0, 8.0, 16384), [-100, -20, -10, 10, 20, 100, 0.0, -0.0]]).astype(np.float32)
+    x = np.zeros((M, K), np.float32)
+    W = np.full((N, K), 0.01, np.float32)
+    qw_ref, sw_ref = oracle.quant_weight(W, 8)
+    ref = oracle.qlinear(x, qw_ref, sw_ref, b, EPI_ORACLE[epi])
+    assert not ref["acc"].any()
+    y = qc.qlinear_t(dev(x), qc.pack_weight_t(dev(W), 8), dev(b), epi, out)
+    y_ref = ref["y"]
+    y_ref = (oracle.bf16_bits_to_f64(oracle.round_bf16_bits(y_ref)) if out == "bf16"
+             else oracle.round_f32(y_ref).astype(np.float64))
+    got = host_f64(y)
+    rtol = RTOL[out]
+    assert np.all(np.abs(got - y_ref) <= rtol * np.abs(y_ref) + rtol), float(np.abs(got - y_ref).max())
+    # the float path is far inside its bar: absolute error of the activation itself
+    if out == "f32":
+        assert float(np.abs(got - y_ref).max()) < 2e-6 * 8
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("K", [100, 200, 1000, 1160])
+def test_qlinear_ragged_k_with_a_poisoned_workspace(bits, K):
+    """K is padded to 192 inside the tiled workspace and the quantizer does not write the
+    padding; the GEMM reads it and multiplies it by the zero padding of the packed weights.
+    With the workspace full of 0x7f bytes beforehand the result must not change."""
+    rng = np.random.default_rng(K + bits)
+    M, N = 300, 200
+    x = random_x(rng, M, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    ref = oracle.qlinear(x, qw_ref, sw_ref, None, oracle.EPI_NONE)
+    ws = qc.qlinear_workspace_t(M, K, N)
+    ws.fill_(0x7f)
+    acc = qc.qlinear_t(dev(x), qc.pack_weight_t(dev(W), bits), None, "none", "i32", workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+
+
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("M,N", [(4096, 4096), (4096 - 37, 4096 - 3)])
 def test_qlinear_many_tiles_full_comparison(bits, M, N):
