@@ -74,6 +74,11 @@ __host__ __device__ inline int64_t w4_dword_offset(int64_t n, int64_t k8, int64_
 __host__ __device__ inline int w4_nibble_of(int e) { return e < 4 ? 2 * e : 2 * (e - 4) + 1; }
 
 // workspace of qc_qlinear: [ x_scale: Mp floats ][ tiled codes: Mp * Kp bytes ]
+// The quantization kernels write rows 0 .. M-1 and columns 0 .. K-1 only.  The GEMM reads whole
+// fragments, padding included: what it finds in columns K .. Kp-1 is multiplied by the zero codes
+// qc_pack_weight stores in the weights' K padding (so any bytes will do), and rows M .. Mp-1 are
+// accumulated and never stored.  Packed weights must therefore always carry zeros in their K
+// padding.
 struct ActWorkspace {
     int64_t Mp, Kp, KF;
     size_t scale_bytes, total_bytes;
