@@ -15,6 +15,28 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
 
 
+def test_traffic_table_names_every_workload_and_its_commit():
+    """bench.py reads roofline.traffic from the tracked profiler summary: every workload must be
+    there with plausible bytes, and the table must say which commit it was measured at."""
+    sys.path.insert(0, ROOT)
+    import bench
+    table, commit = bench.traffic_table()
+    assert commit and len(commit) >= 7
+    assert set(table) == set(bench.WORKLOADS)
+    for name, row in table.items():
+        assert row["gemm"] > 1e8 and row["quant"] > 5e7, name
+    # quantization traffic equals its algorithmic bytes (read 2 B, write 1 B per element + scales)
+    assert abs(table["qkv256"]["quant"] / (16384 * 1152 * 3 + 4 * 16384) - 1) < 0.02
+    assert abs(table["fc2_512_w8"]["quant"] / (65536 * 4608 * 3 + 4 * 65536) - 1) < 0.02
+    # the GEMM never moves less than its algorithmic bytes
+    assert table["fc1_512"]["gemm"] > 65536 * 1152 + 4608 * 1152 + 65536 * 4608 * 2
+
+
+def test_roofs_program_is_built_beside_the_library():
+    assert os.path.exists(os.path.join(ROOT, "bench", "qc_roofs.hip"))
+    assert os.access(os.path.join(ROOT, "bench", "qc_roofs"), os.X_OK), "run python -m paper_2503_06545_amd.build"
+
+
 CONTRACT_KEYS = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
                  "higher_is_better", "scaling", "vs_baseline", "dtype", "data", "config",
                  "roofline", "cpu_baseline")
