@@ -458,7 +458,7 @@ class Bench:
         r["frac_of_traffic_yardstick"] = round(tops / fed, 4) if fed else None
         return r
 
-    def hbm_entry(self, bytes_per_launch, us, roof_key="hbm_copy_gbs", traffic=None):
+    def hbm_entry(self, bytes_per_launch, us, roof_key="hbm_read2_write1_gbs", traffic=None):
         gbs = bytes_per_launch / (us * 1e-6) / 1e9
         roof = self.roofs.get(roof_key)
         return {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",

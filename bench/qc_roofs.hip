@@ -49,6 +49,29 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(const float4 *__restrict_
     }
 }
 
+// Two bytes read for every byte written (the proportions of the activation quantization:
+// bf16 in, int8 out): two float4 loads feed one float4 store.
+template <int THREADS, int U>
+__global__ __launch_bounds__(THREADS) void read2_write1_kernel(const float4 *__restrict__ a,
+                                                               float4 *__restrict__ b, int64_t n4_out) {
+    constexpr int64_t kChunk = (int64_t)THREADS * U;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < n4_out; base += (int64_t)gridDim.x * kChunk) {
+        float4 v[U], w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            const int64_t j = i < n4_out ? i : 0;
+            v[u] = a[2 * j];
+            w[u] = a[2 * j + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * THREADS + threadIdx.x;
+            if (i < n4_out) b[i] = make_float4(v[u].x + w[u].x, v[u].y + w[u].y, v[u].z + w[u].z, v[u].w + w[u].w);
+        }
+    }
+}
+
 // Read-only stream: a block takes contiguous chunks of THREADS * U float4 and strides over the
 // buffer by the grid; the U loads of a lane are all in flight before the first use.
 template <int THREADS, int U>
@@ -281,6 +304,16 @@ int main(int argc, char **argv) {
         printf("hbm  copy, 1 GiB read + 1 GiB written (best of three launch shapes: %.0f / %.0f / %.0f): %7.0f GB/s\n",
                2.0 * n / ms * 1e-6, 2.0 * n / ms2 * 1e-6, 2.0 * n / ms3 * 1e-6, 2.0 * n / cbest * 1e-6);
         printf("@hbm_copy_gbs %.0f\n", 2.0 * n / cbest * 1e-6);
+        {   // 1 GiB read, 512 MiB written
+            const int64_t n4o = n / 32;
+            ms = settled_ms([&] { read2_write1_kernel<256, 2><<<8 * CU, 256>>>(a, b, n4o); });
+            ms2 = settled_ms([&] { read2_write1_kernel<256, 4><<<8 * CU, 256>>>(a, b, n4o); });
+            ms3 = settled_ms([&] { read2_write1_kernel<1024, 2><<<CU, 1024>>>(a, b, n4o); });
+            const float mbest = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
+            printf("hbm  1 GiB read + 512 MiB written, the quantizer's proportions (%.0f / %.0f / %.0f): %7.0f GB/s\n",
+                   1.5 * n / ms * 1e-6, 1.5 * n / ms2 * 1e-6, 1.5 * n / ms3 * 1e-6, 1.5 * n / mbest * 1e-6);
+            printf("@hbm_read2_write1_gbs %.0f\n", 1.5 * n / mbest * 1e-6);
+        }
         // Two 16 MiB buffers per launch (the size of the latent pair), each launch on the next
         // of 12 distinct pairs so that nothing is left in the caches from the launch before, and
         // the same on one pair that stays in the Infinity Cache.  Timed as bench.py times its

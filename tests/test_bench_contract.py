@@ -78,6 +78,8 @@ def test_default_run_is_the_sweep_with_the_single_layer_configurations():
     assert d["device"]["samples"] > 10           # the timed region is long enough to sample
     roofs = d["achievable_roofs"]
     assert 3000 < roofs["hbm_read_gbs"] < 8000 and 3000 < roofs["hbm_copy_gbs"] < 8000
+    assert 3000 < roofs["hbm_read2_write1_gbs"] < 8000
+    assert d["kernels"]["quant_act"]["achievable"] == roofs["hbm_read2_write1_gbs"]
     assert roofs["read_32mib_cold_us"] > roofs["read_32mib_warm_us"] > 1.0
     assert len(d["provenance"]["source_sha16"]) == 16 and d["provenance"]["rocm"]
     cb = d["cpu_baseline"]
