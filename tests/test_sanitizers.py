@@ -53,8 +53,10 @@ def test_oracle_runs_clean_under_asan_and_ubsan(tmp_path):
         oracle.cumulative_variation(a, [c, a])
         print("oracle ok under sanitizers")
     """)
-    env = dict(os.environ, LD_PRELOAD=_asan_runtime(), ASAN_OPTIONS="detect_leaks=0", OMP_NUM_THREADS="2",
-               QC_ORACLE_LIB=str(lib))
+    # the sanitizer runtime has to be the first preloaded library; whatever is preloaded already stays
+    preload = ":".join(p for p in (_asan_runtime(), os.environ.get("LD_PRELOAD", "")) if p)
+    env = dict(os.environ, LD_PRELOAD=preload, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0",
+               OMP_NUM_THREADS="2", QC_ORACLE_LIB=str(lib))
     r = subprocess.run([sys.executable, "-c", script], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0 and "oracle ok under sanitizers" in r.stdout, (r.stdout[-500:], r.stderr[-3000:])
     assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr[-3000:]
