@@ -126,7 +126,7 @@ class LinearCase:
 
 HIDDEN, MLP = 1152, 4608
 
-# benchmark configs[0..3] (config 4 = the 28-block sweep is built from stdit_block_layers)
+# the tiny and the single-layer benchmark configurations (the 28-block sweep is built by stdit_block_layers)
 TINY = LinearCase("tiny_w8a8", M=256, K=HIDDEN, N=HIDDEN, x_dtype="f32", out_dtype="f32",
                   outliers=8)
 QKV_256 = LinearCase("stdit_qkv_256", M=16 * 1024, K=HIDDEN, N=3 * HIDDEN,
