@@ -344,7 +344,8 @@ class Layer:
 class Bench:
     """Everything that is shared between the workloads of one run."""
 
-    def __init__(self, variant, roofs):
+    def __init__(self, variant, roofs, graph=False):
+        self.graph = graph
         import torch
         from paper_2503_06545_amd import binding as qc
         from paper_2503_06545_amd import synth
@@ -578,6 +579,18 @@ class Bench:
             for L in layers:
                 self.qlinear(L)
 
+        eager_step = step
+        if self.graph:
+            # The 224 launches of a step recorded once into a HIP graph (no entry point
+            # allocates, clears or needs a set-up call, so the calls can be captured as they
+            # are) and replayed: the step then costs one submission instead of 224.
+            torch.cuda.synchronize()
+            g, cap = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+            main_stream, self.stream = self.stream, cap.cuda_stream   # the calls go to the capturing stream
+            with torch.cuda.graph(g, stream=cap):
+                eager_step()
+            self.stream = main_stream
+            step = g.replay
         preload(step)
         for _ in range(warmup):
             step()
@@ -651,6 +664,8 @@ def main():
                     help="activation quantizer: a8 (default), a6 / a4 (lower bit-widths), rot128 "
                          "(Walsh-Hadamard rotation of 128-column blocks fused in), asym (zero "
                          "point per token)")
+    ap.add_argument("--graph", action="store_true",
+                    help="sweep28: record the step's launches once into a HIP graph and time replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true",
                     help="sweep28 only: skip the single-layer configurations")
@@ -678,7 +693,7 @@ def main():
     sweep = args.workload == "sweep28"
     steps = args.steps if args.steps is not None else (20 if sweep else 300)
     warmup = args.warmup if args.warmup is not None else (5 if sweep else 100)
-    bench = Bench(args.variant, roofs)
+    bench = Bench(args.variant, roofs, args.graph)
 
     configs = {}
     if sweep:
