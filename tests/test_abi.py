@@ -195,3 +195,23 @@ def test_decision_rules_match_the_oracle_on_every_case_and_boundary():
     assert math.isnan(qc.qc_prune_probability(nan, 0.8, 0.95, 0.25))
     assert math.isnan(qc.qc_prune_probability(0.9, 0.95, 0.8, 0.25))
     assert math.isnan(qc.qc_divergence_score(1.0, 0, 1.0))
+
+
+def test_build_reads_the_compilers_resource_remarks():
+    """build.py fails when a kernel needs scratch memory; its parser of the compiler's remarks
+    must find the kernel name, the VGPR count, the scratch bytes and the occupancy."""
+    from paper_2503_06545_amd import build as qc_build
+    text = (
+        "csrc/x.hip:9:1: remark: Function Name: _ZN2qc4kernEv [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:9:1: remark:     VGPRs: 212 [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:9:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:9:1: remark:     Occupancy [waves/SIMD]: 2 [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:40:1: remark: Function Name: _ZN2qc5spillEv [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:40:1: remark:     VGPRs: 256 [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:40:1: remark:     ScratchSize [bytes/lane]: 76 [-Rpass-analysis=kernel-resource-usage]\n"
+        "csrc/x.hip:40:1: remark:     Occupancy [waves/SIMD]: 2 [-Rpass-analysis=kernel-resource-usage]\n")
+    assert qc_build._resources(text) == [("_ZN2qc4kernEv", 212, 0, 2), ("_ZN2qc5spillEv", 256, 76, 2)]
+    # the report of the library that is built here: every kernel, none with scratch memory
+    report = open(qc_build.RESOURCE_REPORT).read().splitlines()
+    assert len(report) >= 60 and all("scratch_bytes_per_lane=0" in line for line in report)
+    assert sum("gemm_kernel" in line for line in report) == 26
