@@ -518,7 +518,10 @@ hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8
     // the patch in that XCD's L2; with few (all of them resident at once anyway) a narrow patch
     // launches the blocks that share a token panel next to each other, so that they read it at
     // the same time (fc2, 9 channel tiles, K = 4608: 870 MB instead of 1370 MB fetched by the L2s).
-    args.group_m = args.n_tiles <= 16 ? 2 : 8;
+    // Measured at M = 131072: 8 is the best of 4 .. 32 for the wide layers; for the narrow ones
+    // 2 is the best of 1 .. 8 at K = 1152 and 3 the best of 2 .. 6 at K = 4608 (545 against
+    // 557 us with 8-bit weights, no difference at M = 65536 or with 4-bit weights).
+    args.group_m = args.n_tiles > 16 ? 8 : (args.KF >= 36 ? 3 : 2);
     if (x_corr && w_rowsum)
         return bits == 8 ? launch_bits<8, true>(args, epi, ydt, stream)
                          : launch_bits<4, true>(args, epi, ydt, stream);
