@@ -652,6 +652,44 @@ class Bench:
         return res, cases
 
 
+def library_int8_gemm(cases):
+    """The vendor library's int8 GEMM (torch._int_mm: int8 x int8 -> int32, nothing fused) on the
+    distinct (M, K, N) of the workload and on one large square, with uniform random int8 operands,
+    after the same 0.3 s of load.  Only a yardstick: it shows what rate the library's own kernels
+    hold on this chip under its power cap; its output is 4 bytes per element where the path's
+    epilogue writes 2."""
+    import torch
+
+    out = {"what": "torch._int_mm, int32 out, uniform random int8 operands", "shapes": {}}
+    shapes = sorted({(c.M, c.K, c.N) for c in cases}) + [(8192, 8192, 8192)]
+    for M, K, N in shapes:
+        a = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda")
+        b = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda").t()
+        try:
+            torch._int_mm(a, b)
+        except RuntimeError as e:
+            out["shapes"][f"{M}x{K}x{N}"] = {"error": str(e)[:120]}
+            continue
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < PRELOAD_SECONDS:
+            torch._int_mm(a, b)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        iters = 30
+        e0.record()
+        for _ in range(iters):
+            torch._int_mm(a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        tops = 2.0 * M * N * K / (us * 1e-6) / 1e12
+        out["shapes"][f"{M}x{K}x{N}"] = {"avg_us": round(us, 1), "tops": round(tops, 1),
+                                         "frac": round(tops / PEAK_INT8_TOPS, 4)}
+        del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -670,6 +708,10 @@ def main():
     ap.add_argument("--no-configs", action="store_true",
                     help="sweep28 only: skip the single-layer configurations")
     ap.add_argument("--no-roofs", action="store_true", help="do not run bench/qc_roofs first")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the int8 GEMM of the library that ships with ROCm (through "
+                         "torch._int_mm, int32 output, no scales / bias / GELU) on the workload's "
+                         "shapes: a yardstick for the power-limited MFMA rate, not a part of the path")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 256 MiB device copies, as the reference kernel "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -708,6 +750,8 @@ def main():
     else:
         head, case = bench.run_single(args.workload, steps, warmup)
         cases = [case]
+
+    library = library_int8_gemm(cases) if args.library_gemm else None
 
     if args.calibration_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -749,6 +793,8 @@ def main():
         result["config"].update({"K": c.K, "N": c.N, "weight_bits": c.bits, "epilogue": c.epi})
     if configs:
         result["configs"] = configs
+    if library is not None:
+        result["library_int8_gemm"] = library
     if not args.no_cpu_baseline:
         if sweep:
             result["cpu_baseline"] = cpu_baseline_sweep(cases, bench.act_bits, bench.rot, bench.asym)

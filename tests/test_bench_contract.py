@@ -103,8 +103,12 @@ def test_default_run_is_the_sweep_with_the_single_layer_configurations():
 
 @pytest.mark.gpu
 def test_single_layer_headline_with_another_activation_quantizer():
-    d = run_bench(["--workload", "qkv256", "--variant", "asym", "--steps", "20", "--warmup", "20"])
+    d = run_bench(["--workload", "qkv256", "--variant", "asym", "--steps", "20", "--warmup", "20",
+                   "--library-gemm"])
     assert d["steps"] == 20 and d["warmup"] == 20 and "configs" not in d
+    lib = d["library_int8_gemm"]["shapes"]
+    assert set(lib) == {"16384x1152x3456", "8192x8192x8192"}
+    assert all("error" in v or 0 < v["frac"] < 1 for v in lib.values())
     check_roofline(d["roofline"])
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
