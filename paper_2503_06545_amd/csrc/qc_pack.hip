@@ -238,6 +238,7 @@ extern "C" qc_status qc_unpack_weight_codes(const void *packed, int64_t N, int64
     if (qc_packed_weight_bytes(N, K, bits) == 0) return QC_ERR_UNSUPPORTED;
     const int64_t Kp = round_up(K, kKAlign);
     const int64_t blocks = (N * K + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     unpack_weight_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
         (const uint8_t *)packed, N, K, bits, Kp, codes);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
@@ -251,6 +252,7 @@ extern "C" qc_status qc_debug_workspace_act(const void *workspace, int64_t M, in
     const ActWorkspace ws = act_workspace(M, K);
     const uint8_t *base = (const uint8_t *)workspace;
     const int64_t blocks = (M * K + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     untile_act_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
         base + ws.scale_bytes, (const float *)base, M, K, ws.KF, qx, x_scale);
     return hipGetLastError() == hipSuccess ? QC_OK : QC_ERR_DEVICE;
@@ -278,6 +280,7 @@ extern "C" qc_status qc_debug_workspace_act_asym(const void *workspace, int64_t 
     const ActWorkspaceAsym ws = act_workspace_asym(M, K);
     const uint8_t *base = (const uint8_t *)workspace;
     const int64_t blocks = (M * K + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return QC_ERR_UNSUPPORTED;
     untile_act_asym_kernel<<<dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream>>>(
         base + ws.codes_offset, (const float *)base, (const float *)(base + ws.corr_offset), M, K,
         ws.sym.KF, asym_code_shift(act_bits), qx, x_scale, x_zero);

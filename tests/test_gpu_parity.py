@@ -540,6 +540,47 @@ def test_config_sweep28_sampled_rows(kind, bits):
         _sweep_x.clear()
 
 
+def test_qlinear_offsets_beyond_4_gib():
+    """A problem whose input passes 2 GiB and whose output passes 4 GiB, so that a 32-bit byte or
+    element offset anywhere on the path would wrap: M = 2^19 + 77 tokens of 1152 binary32 values
+    (2.4 GB), 2304 channels of binary32 output (4.8 GB), and the same again as raw accumulators.
+    X repeats a block of 8192 generated rows (tokens are independent), so the oracle runs on
+    sampled rows of that block and every output row must also equal, bit for bit, the row 8192
+    above it."""
+    period, M, K, N = 8192, (1 << 19) + 77, 1152, 2304
+    case = synth.LinearCase("offsets", M=period, K=K, N=N, x_dtype="f32", out_dtype="f32", outliers=12, seed=5)
+    x_block = case.x()
+    W, b = case.weight(), case.bias()
+    xd = dev(x_block).repeat((M + period - 1) // period, 1)[:M].contiguous()
+    assert xd.numel() * 4 > 1 << 31 and M * N * 4 > 1 << 32
+    pw = qc.pack_weight_t(dev(W), 8)
+    ws = qc.qlinear_workspace_t(M, K, N)
+    y = qc.qlinear_t(xd, pw, dev(b), "none", "f32", workspace=ws)
+    acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+    qx, sx = qc.debug_workspace_act_t(ws, M, K)
+    torch.cuda.synchronize()
+    assert y.shape == (M, N) and acc.shape == (M, N)
+    # rows next to the byte offsets 2^31 and 2^32 of X, of Y and of the code workspace
+    edges = {0, 1, M - 1, M - 2, M - 77, M - 78}
+    for row_bytes in (4 * K, 4 * N, K):
+        for boundary in (1 << 30, 1 << 31, 1 << 32):
+            r = boundary // row_bytes
+            edges.update(q for q in (r - 1, r, r + 1) if 0 <= q < M)
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([np.fromiter(edges, np.int64), rng.integers(0, M, 40)]))
+    ridx = torch.from_numpy(rows).cuda()
+    qw_ref, sw_ref = oracle.quant_weight(W, 8)
+    ref = oracle.qlinear(x_block[rows % period], qw_ref, sw_ref, b, oracle.EPI_NONE)
+    assert bits_equal(sx[ridx].cpu().numpy(), ref["sx"])
+    assert np.array_equal(qx[ridx].cpu().numpy(), ref["qx"])
+    assert np.array_equal(acc[ridx].cpu().numpy(), ref["acc"])
+    assert_outputs_close(host_f64(y[ridx]), ref["y"].astype(np.float64), RTOL["f32"])
+    # every row against the one a period above it
+    assert torch.equal(acc[period:], acc[:-period])
+    assert torch.equal(y[period:].view(torch.int32), y[:-period].view(torch.int32))
+    assert torch.equal(sx[period:M].view(torch.int32), sx[:M - period].view(torch.int32))
+
+
 # ------------------------------------------------------------------ qc_latent_delta
 
 @pytest.mark.parametrize("n", [1, 3, 4, 5, 1023, 4096, 100003, 16 * 4 * 16 * 64 * 64, 9_000_001])
@@ -653,6 +694,55 @@ def test_cumulative_variation_agrees_with_latent_delta_and_closed_forms():
     one = qc.cumulative_variation_t(a, [b]).cpu().numpy()
     pair = qc.latent_delta_t(a, b).cpu().numpy()
     assert abs(one[0] - pair[0]) <= 1e-6 * pair[0] and one[1] == one[0]
+
+
+def test_reductions_past_2_to_the_31_elements():
+    """Tensors of 2^31 + 4099 elements (8.6 GB each): an element or byte index held in 32 bits
+    anywhere in the reduction kernels would wrap.  The tensors repeat a generated block of 2^20
+    elements 2048 times and end with its first 4099, so every sum is 2048 times the oracle's sum
+    over the block plus its sum over that tail."""
+    P, reps, tail = 1 << 20, 2048, 4099
+    n = reps * P + tail
+    assert n > 1 << 31
+    cur_b, prev_b = synth.latent_pair(seed=9, n=P, delta=0.05)
+
+    def tiled(block, length):
+        t = torch.empty(length, dtype=torch.float32, device="cuda")
+        full = length // P
+        t[:full * P].view(full, P).copy_(dev(block)[None, :].expand(full, P))
+        t[full * P:] = dev(block)[:length - full * P]
+        return t
+
+    def combined(fn, tail_len, *blocks):
+        whole = np.asarray(fn(*blocks), np.float64)
+        part = np.asarray(fn(*(b[..., :tail_len] for b in blocks)), np.float64)
+        return reps * whole + part
+
+    cur, prev = tiled(cur_b, n), tiled(prev_b, n)
+
+    ref = combined(oracle.latent_delta, tail, cur_b, prev_b)       # the ratio is redone below
+    got = qc.latent_delta_t(cur, prev).cpu().numpy().astype(np.float64)
+    assert abs(got[0] - ref[0]) <= 1e-5 * ref[0] and abs(got[1] - ref[1]) <= 1e-5 * ref[1]
+    assert abs(got[2] - ref[0] / ref[1]) <= 1e-5 * ref[0] / ref[1]
+
+    ref = combined(oracle.layer_similarity, tail, cur_b, prev_b)
+    got = qc.layer_similarity_t(cur, prev).cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got[:3] - ref[:3]) <= 1e-6 * np.abs(ref[:3]))
+    assert abs(got[3] - ref[0] / math.sqrt(ref[1] * ref[2])) <= 2e-6
+
+    got = qc.cumulative_variation_t(cur, [prev, prev]).cpu().numpy().astype(np.float64)
+    num = combined(oracle.latent_delta, tail, cur_b, prev_b)[0]
+    assert np.all(np.abs(got - np.array([num, num, 2 * num])) <= 1e-5 * num)
+    del cur, prev
+
+    inner = reps * P + 4096                                           # a multiple of 8: vector path
+    frames = torch.empty((2, inner), dtype=torch.float32, device="cuda")
+    frames[0], frames[1] = tiled(prev_b, inner), tiled(cur_b, inner)
+    ss = combined(lambda m: oracle.frame_gradient(m)[:1], 4096, np.stack([prev_b, cur_b]))[0]
+    got = qc.frame_gradient_norm_t(frames).cpu().numpy().astype(np.float64)
+    assert abs(got[0] - ss) <= 2e-6 * ss and abs(got[1] - math.sqrt(ss)) <= 2e-6 * math.sqrt(ss)
+    del frames
+    torch.cuda.empty_cache()
 
 
 # ------------------------------------------------------------------ rotation fused into quantization
@@ -847,6 +937,52 @@ def test_quant_act_tensor_bit_exact(act_bits, dtype, M, K):
     torch.cuda.synchronize()
     assert bits_equal(sx.cpu().numpy(), np.array([s_ref], np.float32))
     assert np.array_equal(qx.cpu().numpy(), q_ref)
+
+
+@pytest.mark.parametrize("how", ["token", "rot128", "asym", "tensor"])
+def test_quantizers_offsets_beyond_4_gib(how):
+    """2^19 + 5 rows of 4608 bf16 values: 4.8 GB of input and 2.4 GB of codes, past what 32-bit
+    byte offsets reach, on the kernel that cuts a row into four column slices.  X repeats a
+    generated block of 2048 rows, so the oracle's codes for the block are the expected codes of
+    every repetition (for the one-scale-per-tensor form too: the tensor's absmax is the block's)."""
+    period, M, K = 2048, (1 << 19) + 5, 4608
+    block = random_x(np.random.default_rng(23), period, K, "bf16")
+    xd = dev(block).repeat((M + period - 1) // period, 1)[:M].contiguous()
+    assert xd.numel() * 2 > 1 << 32 and xd.numel() > 1 << 31
+    aux = None
+    if how == "token":
+        q_ref, s_ref = oracle.quant_act(block)
+        qx, sx = qc.quant_act_t(xd)
+    elif how == "rot128":
+        q_ref, s_ref = oracle.quant_act_rot(block, 128, 8)
+        qx, sx = qc.quant_act_t(xd, 8, 128)
+    elif how == "asym":
+        q_ref, s_ref, z_ref = oracle.quant_act_asym(block, 8)
+        qx, sx, aux = qc.quant_act_asym_t(xd, 8)
+    else:
+        q_ref, s_one = oracle.quant_act_tensor(block, 8)
+        s_ref = None
+        qx, sx = qc.quant_act_tensor_t(xd, 8)
+        assert bits_equal(sx.cpu().numpy(), np.array([s_one], np.float32))
+    torch.cuda.synchronize()
+    del xd
+    q_ref_d = torch.from_numpy(q_ref.view(np.int8)).cuda()
+    reps, rest = divmod(M, period)
+    codes = qx.view(torch.int8)
+    assert torch.equal(codes[:reps * period].view(reps, period, K), q_ref_d[None].expand(reps, period, K))
+    assert torch.equal(codes[reps * period:], q_ref_d[:rest])
+    if s_ref is not None:
+        s_ref_d = torch.from_numpy(s_ref.view(np.int32)).cuda()
+        bits = sx.view(torch.int32)
+        assert torch.equal(bits[:reps * period].view(reps, period), s_ref_d[None].expand(reps, period))
+        assert torch.equal(bits[reps * period:], s_ref_d[:rest])
+    if aux is not None:
+        z_ref_d = torch.from_numpy(z_ref.view(np.int32)).cuda()
+        bits = aux.view(torch.int32)
+        assert torch.equal(bits[:reps * period].view(reps, period), z_ref_d[None].expand(reps, period))
+        assert torch.equal(bits[reps * period:], z_ref_d[:rest])
+    del qx, sx, codes
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("bits,act_bits", [(8, 8), (4, 8), (4, 6)])
