@@ -652,24 +652,24 @@ class Bench:
         return res, cases
 
 
-def library_int8_gemm(cases):
+def library_int8_gemm(bench, cases):
     """The vendor library's int8 GEMM (torch._int_mm: int8 x int8 -> int32, nothing fused) on the
-    distinct (M, K, N) of the workload and on one large square, with uniform random int8 operands,
-    after the same 0.3 s of load.  Only a yardstick: it shows what rate the library's own kernels
-    hold on this chip under its power cap; its output is 4 bytes per element where the path's
-    epilogue writes 2."""
+    distinct (M, K, N) of the workload, fed with the very codes this library's quantizers produce
+    for the workload's activations and weights (operand values decide how much power an MFMA
+    draws), after the same 0.3 s of load; and on one large square, with such codes and with
+    uniform random bytes.  Only a yardstick: it shows what rate the library's own kernels hold on
+    this chip under its power cap; its output is 4 bytes per element where the path's epilogue
+    writes 2."""
     import torch
+    qc = bench.qc
 
-    out = {"what": "torch._int_mm, int32 out, uniform random int8 operands", "shapes": {}}
-    shapes = sorted({(c.M, c.K, c.N) for c in cases}) + [(8192, 8192, 8192)]
-    for M, K, N in shapes:
-        a = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda")
-        b = torch.randint(-127, 128, (N, K), dtype=torch.int8, device="cuda").t()
+    def timed(a, b):
+        M, K = a.shape
+        N = b.shape[1]
         try:
             torch._int_mm(a, b)
         except RuntimeError as e:
-            out["shapes"][f"{M}x{K}x{N}"] = {"error": str(e)[:120]}
-            continue
+            return {"error": str(e)[:120]}
         t0 = time.perf_counter()
         while time.perf_counter() - t0 < PRELOAD_SECONDS:
             torch._int_mm(a, b)
@@ -683,9 +683,54 @@ def library_int8_gemm(cases):
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / iters
         tops = 2.0 * M * N * K / (us * 1e-6) / 1e12
-        out["shapes"][f"{M}x{K}x{N}"] = {"avg_us": round(us, 1), "tops": round(tops, 1),
-                                         "frac": round(tops / PEAK_INT8_TOPS, 4)}
+        return {"avg_us": round(us, 1), "tops": round(tops, 1), "frac": round(tops / PEAK_INT8_TOPS, 4)}
+
+    def codes(x_bf16, w_f32, bits):
+        a = qc.quant_act_t(x_bf16, 8)[0]
+        b = qc.unpack_weight_codes_t(qc.pack_weight_t(w_f32, bits))
+        return a, b.t()
+
+    out = {"what": "torch._int_mm, int32 out; operands: the codes of the workload's own activations "
+                   "and weights", "shapes": {}}
+    seen = set()
+    for layer, c in enumerate(cases):
+        if (c.M, c.K, c.N) in seen:
+            continue
+        seen.add((c.M, c.K, c.N))
+        a, b = codes(bench.activations(c), torch.from_numpy(c.weight(layer)).cuda(), c.bits)
+        out["shapes"][f"{c.M}x{c.K}x{c.N}"] = dict(timed(a, b), weight_bits=c.bits)
         del a, b
+    n = 8192
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    x = torch.randn((n, n), device="cuda", generator=gen).to(torch.bfloat16)
+    w = torch.randn((n, n), device="cuda", generator=gen) * 0.02
+    a, b = codes(x, w, 8)
+    out["square_8192"] = {"codes_of_normal_data": timed(a, b)}
+    a = torch.randint(-127, 128, (n, n), dtype=torch.int8, device="cuda", generator=gen)
+    b = torch.randint(-127, 128, (n, n), dtype=torch.int8, device="cuda", generator=gen).t()
+    out["square_8192"]["uniform_random_bytes"] = timed(a, b)
+    # the same square through this library's GEMM stage (bf16 out, no activation)
+    pw = qc.pack_weight_t(w, 8)
+    ws = qc.qlinear_workspace_t(n, n, n)
+    bias = torch.zeros(n, device="cuda")
+    y = qc.qlinear_t(x, pw, bias, "none", "bf16", workspace=ws)
+    args = (ws.data_ptr(), ws.numel(), n, n, pw.blob.data_ptr(), pw.scale.data_ptr(), 8, n,
+            bias.data_ptr(), qc.QC_EPI_NONE, y.data_ptr(), qc.QC_OUT_BF16, bench.stream)
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < PRELOAD_SECONDS:
+        bench.check(qc.qc_qlinear_gemm(*args))
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(30):
+        bench.check(qc.qc_qlinear_gemm(*args))
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / 30
+    tops = 2.0 * n ** 3 / (us * 1e-6) / 1e12
+    out["square_8192"]["qc_qlinear_gemm"] = {"avg_us": round(us, 1), "tops": round(tops, 1),
+                                             "frac": round(tops / PEAK_INT8_TOPS, 4)}
+    del a, b, x, w, y, ws
     torch.cuda.empty_cache()
     return out
 
@@ -751,7 +796,7 @@ def main():
         head, case = bench.run_single(args.workload, steps, warmup)
         cases = [case]
 
-    library = library_int8_gemm(cases) if args.library_gemm else None
+    library = library_int8_gemm(bench, cases) if args.library_gemm else None
 
     if args.calibration_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
