@@ -519,8 +519,9 @@ class Bench:
                 "quant_act": self.hbm_entry(quant_bytes, quant["avg_us"], traffic=tr.get("quant")),
                 "latent_delta": dict(self.hbm_entry(delta_bytes, delta["avg_us"], "hbm_read_gbs",
                                                     traffic=tr.get("delta")),
-                                     note="two launches per call; the 33.5 MB of inputs stay resident in "
-                                          "the 256 MB Infinity Cache between calls (warm)"),
+                                     note="two launches per call; the same 33.5 MB pair on every call (it "
+                                          "fits the 256 MB Infinity Cache, but the kernel's non-temporal "
+                                          "loads do not leave it there)"),
                 "pack_weight_offline": {"avg_launch_us": round(pack["avg_us"], 2)},
                 # quantization + GEMM + epilogue of the layer, without the latent delta
                 "qlinear_whole_call": {

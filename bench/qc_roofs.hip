@@ -8,6 +8,7 @@
 // cold 32 MiB read, the 16x16x64 MFMA loop).  Each measurement runs for several tens of
 // milliseconds so that the clocks have settled.
 #include <hip/hip_runtime.h>
+#include <initializer_list>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -29,8 +30,29 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ---- HBM ---------------------------------------------------------------------------------
+// POLICY bit 0: non-temporal loads, bit 1: non-temporal stores.  For buffers far larger than the
+// caches, as here, what a pass leaves in them only costs; every roof below is the best over the
+// launch shapes and these policies.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int POLICY>
+__device__ inline float4 ld16(const float4 *p) {
+    if constexpr (POLICY & 1) {
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        return make_float4(v.x, v.y, v.z, v.w);
+    } else {
+        return *p;
+    }
+}
+
+template <int POLICY>
+__device__ inline void st16(float4 *p, const float4 &v) {
+    if constexpr (POLICY & 2) __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(p));
+    else *p = v;
+}
+
 // Copy: like the read stream below, U loads of a lane in flight, then its U stores.
-template <int THREADS, int U>
+template <int THREADS, int U, int POLICY = 0>
 __global__ __launch_bounds__(THREADS) void copy_kernel(const float4 *__restrict__ a,
                                                        float4 *__restrict__ b, int64_t n4) {
     constexpr int64_t kChunk = (int64_t)THREADS * U;
@@ -39,19 +61,19 @@ __global__ __launch_bounds__(THREADS) void copy_kernel(const float4 *__restrict_
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
-            v[u] = a[i < n4 ? i : 0];
+            v[u] = ld16<POLICY>(a + (i < n4 ? i : 0));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
-            if (i < n4) b[i] = v[u];
+            if (i < n4) st16<POLICY>(b + i, v[u]);
         }
     }
 }
 
 // Two bytes read for every byte written (the proportions of the activation quantization:
 // bf16 in, int8 out): two float4 loads feed one float4 store.
-template <int THREADS, int U>
+template <int THREADS, int U, int POLICY = 0>
 __global__ __launch_bounds__(THREADS) void read2_write1_kernel(const float4 *__restrict__ a,
                                                                float4 *__restrict__ b, int64_t n4_out) {
     constexpr int64_t kChunk = (int64_t)THREADS * U;
@@ -61,20 +83,21 @@ __global__ __launch_bounds__(THREADS) void read2_write1_kernel(const float4 *__r
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
             const int64_t j = i < n4_out ? i : 0;
-            v[u] = a[2 * j];
-            w[u] = a[2 * j + 1];
+            v[u] = ld16<POLICY>(a + 2 * j);
+            w[u] = ld16<POLICY>(a + 2 * j + 1);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
-            if (i < n4_out) b[i] = make_float4(v[u].x + w[u].x, v[u].y + w[u].y, v[u].z + w[u].z, v[u].w + w[u].w);
+            if (i < n4_out)
+                st16<POLICY>(b + i, make_float4(v[u].x + w[u].x, v[u].y + w[u].y, v[u].z + w[u].z, v[u].w + w[u].w));
         }
     }
 }
 
 // Read-only stream: a block takes contiguous chunks of THREADS * U float4 and strides over the
 // buffer by the grid; the U loads of a lane are all in flight before the first use.
-template <int THREADS, int U>
+template <int THREADS, int U, int POLICY = 0>
 __global__ __launch_bounds__(THREADS) void read_kernel(const float4 *__restrict__ a, float *out,
                                                        int64_t n4) {
     float s = 0;
@@ -84,7 +107,7 @@ __global__ __launch_bounds__(THREADS) void read_kernel(const float4 *__restrict_
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
-            v[u] = a[i < n4 ? i : 0];
+            v[u] = ld16<POLICY>(a + (i < n4 ? i : 0));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) s += v[u].x + v[u].w;
@@ -290,28 +313,49 @@ int main(int argc, char **argv) {
         CK(hipMalloc(&b, n));
         CK(hipMemset(a, 1, n));
         CK(hipMemset(b, 2, n));
-        float ms = settled_ms([&] { read_kernel<256, 4><<<16384, 256>>>(a, (float *)dout, n / 16); });
-        float ms2 = settled_ms([&] { read_kernel<1024, 4><<<CU, 1024>>>(a, (float *)dout, n / 16); });
-        float ms3 = settled_ms([&] { read_kernel<256, 8><<<8 * CU, 256>>>(a, (float *)dout, n / 16); });
-        const float best = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
-        printf("hbm  read-only stream, 1 GiB (best of three launch shapes: %.0f / %.0f / %.0f): %7.0f GB/s\n",
-               n / ms * 1e-6, n / ms2 * 1e-6, n / ms3 * 1e-6, n / best * 1e-6);
+        auto best_of = [](std::initializer_list<float> ms) {
+            float b = 1e30f;
+            for (float m : ms) b = m < b ? m : b;
+            return b;
+        };
+        float *fout = (float *)dout;
+        const int64_t n4 = n / 16;
+        float ms = settled_ms([&] { read_kernel<256, 4><<<16384, 256>>>(a, fout, n4); });
+        float ms2 = settled_ms([&] { read_kernel<1024, 4><<<CU, 1024>>>(a, fout, n4); });
+        float ms3 = settled_ms([&] { read_kernel<256, 8><<<8 * CU, 256>>>(a, fout, n4); });
+        float ms4 = settled_ms([&] { read_kernel<1024, 4, 1><<<CU, 1024>>>(a, fout, n4); });
+        float ms5 = settled_ms([&] { read_kernel<256, 8, 1><<<8 * CU, 256>>>(a, fout, n4); });
+        const float best = best_of({ms, ms2, ms3, ms4, ms5});
+        printf("hbm  read-only stream, 1 GiB (three launch shapes: %.0f / %.0f / %.0f; the last two with "
+               "non-temporal loads: %.0f / %.0f): %7.0f GB/s\n",
+               n / ms * 1e-6, n / ms2 * 1e-6, n / ms3 * 1e-6, n / ms4 * 1e-6, n / ms5 * 1e-6, n / best * 1e-6);
         printf("@hbm_read_gbs %.0f\n", n / best * 1e-6);
-        ms = settled_ms([&] { copy_kernel<256, 1><<<65536, 256>>>(a, b, n / 16); });
-        ms2 = settled_ms([&] { copy_kernel<256, 4><<<8 * CU, 256>>>(a, b, n / 16); });
-        ms3 = settled_ms([&] { copy_kernel<1024, 4><<<CU, 1024>>>(a, b, n / 16); });
-        const float cbest = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
-        printf("hbm  copy, 1 GiB read + 1 GiB written (best of three launch shapes: %.0f / %.0f / %.0f): %7.0f GB/s\n",
-               2.0 * n / ms * 1e-6, 2.0 * n / ms2 * 1e-6, 2.0 * n / ms3 * 1e-6, 2.0 * n / cbest * 1e-6);
+        ms = settled_ms([&] { copy_kernel<256, 1><<<65536, 256>>>(a, b, n4); });
+        ms2 = settled_ms([&] { copy_kernel<256, 4><<<8 * CU, 256>>>(a, b, n4); });
+        ms3 = settled_ms([&] { copy_kernel<1024, 4><<<CU, 1024>>>(a, b, n4); });
+        ms4 = settled_ms([&] { copy_kernel<256, 4, 1><<<8 * CU, 256>>>(a, b, n4); });
+        ms5 = settled_ms([&] { copy_kernel<256, 4, 2><<<8 * CU, 256>>>(a, b, n4); });
+        float ms6 = settled_ms([&] { copy_kernel<256, 4, 3><<<8 * CU, 256>>>(a, b, n4); });
+        const float cbest = best_of({ms, ms2, ms3, ms4, ms5, ms6});
+        printf("hbm  copy, 1 GiB read + 1 GiB written (three launch shapes: %.0f / %.0f / %.0f; the second "
+               "with non-temporal loads / stores / both: %.0f / %.0f / %.0f): %7.0f GB/s\n",
+               2.0 * n / ms * 1e-6, 2.0 * n / ms2 * 1e-6, 2.0 * n / ms3 * 1e-6, 2.0 * n / ms4 * 1e-6,
+               2.0 * n / ms5 * 1e-6, 2.0 * n / ms6 * 1e-6, 2.0 * n / cbest * 1e-6);
         printf("@hbm_copy_gbs %.0f\n", 2.0 * n / cbest * 1e-6);
         {   // 1 GiB read, 512 MiB written
             const int64_t n4o = n / 32;
             ms = settled_ms([&] { read2_write1_kernel<256, 2><<<8 * CU, 256>>>(a, b, n4o); });
             ms2 = settled_ms([&] { read2_write1_kernel<256, 4><<<8 * CU, 256>>>(a, b, n4o); });
             ms3 = settled_ms([&] { read2_write1_kernel<1024, 2><<<CU, 1024>>>(a, b, n4o); });
-            const float mbest = ms < ms2 ? (ms < ms3 ? ms : ms3) : (ms2 < ms3 ? ms2 : ms3);
-            printf("hbm  1 GiB read + 512 MiB written, the quantizer's proportions (%.0f / %.0f / %.0f): %7.0f GB/s\n",
-                   1.5 * n / ms * 1e-6, 1.5 * n / ms2 * 1e-6, 1.5 * n / ms3 * 1e-6, 1.5 * n / mbest * 1e-6);
+            ms4 = settled_ms([&] { read2_write1_kernel<256, 4, 1><<<8 * CU, 256>>>(a, b, n4o); });
+            ms5 = settled_ms([&] { read2_write1_kernel<256, 4, 2><<<8 * CU, 256>>>(a, b, n4o); });
+            ms6 = settled_ms([&] { read2_write1_kernel<256, 4, 3><<<8 * CU, 256>>>(a, b, n4o); });
+            const float mbest = best_of({ms, ms2, ms3, ms4, ms5, ms6});
+            printf("hbm  1 GiB read + 512 MiB written, the quantizer's proportions (three launch shapes: "
+                   "%.0f / %.0f / %.0f; the second with non-temporal loads / stores / both: %.0f / %.0f / %.0f): "
+                   "%7.0f GB/s\n",
+                   1.5 * n / ms * 1e-6, 1.5 * n / ms2 * 1e-6, 1.5 * n / ms3 * 1e-6, 1.5 * n / ms4 * 1e-6,
+                   1.5 * n / ms5 * 1e-6, 1.5 * n / ms6 * 1e-6, 1.5 * n / mbest * 1e-6);
             printf("@hbm_read2_write1_gbs %.0f\n", 1.5 * n / mbest * 1e-6);
         }
         // Two 16 MiB buffers per launch (the size of the latent pair), each launch on the next

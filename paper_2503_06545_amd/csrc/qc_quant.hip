@@ -12,6 +12,8 @@
 // can round to a non-zero code (Markstein's correction step: one suffices when the reciprocal
 // is correctly rounded; checked against true division on the CPU over all bf16 inputs, random
 // binary32 ones, constructed near-ties and the scales whose significand is all ones).
+#include <type_traits>
+
 #include "qc_internal.h"
 
 namespace qc {
@@ -20,6 +22,33 @@ namespace {
 constexpr int kGenericThreads = 256;
 constexpr int kUnit = 16;          // elements handled as one unit: 16 codes = one 16 B store
 constexpr int kUnitsPerThread = 9; // units held by one lane
+
+// How a kernel treats the caches on its one pass (picked per call by cache_policy()): the chip's
+// last-level cache in front of HBM holds 256 MiB, and what the pass leaves in it decides whether
+// the GEMM that follows finds the codes there.
+enum CachePolicy {
+    kCachePlain = 0,    // input and codes both fit: ordinary loads and stores
+    kStreamLoads = 1,   // the codes fit, not the input beside them: non-temporal loads of X
+    kStreamStores = 2,  // the codes do not fit either: non-temporal stores of the codes
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ inline uint4 load16(const void *p) {
+    if constexpr (NT) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+        return make_uint4(v.x, v.y, v.z, v.w);
+    } else {
+        return *reinterpret_cast<const uint4 *>(p);
+    }
+}
+
+template <bool NT>
+__device__ inline void store16(void *p, const uint4 &v) {
+    if constexpr (NT) __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+    else *reinterpret_cast<uint4 *>(p) = v;
+}
 
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
@@ -31,10 +60,13 @@ struct Unit;
 template <>
 struct Unit<float> {
     float4 v[4];
+    template <bool NT>
     __device__ void load(const float *p) {
-        const float4 *q = reinterpret_cast<const float4 *>(p);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = q[i];
+        for (int i = 0; i < 4; ++i) {
+            const uint4 w = load16<NT>(p + 4 * i);
+            v[i] = make_float4(__uint_as_float(w.x), __uint_as_float(w.y), __uint_as_float(w.z), __uint_as_float(w.w));
+        }
     }
     __device__ void zero() {
 #pragma unroll
@@ -49,10 +81,10 @@ struct Unit<float> {
 template <>
 struct Unit<uint16_t> {  // bf16 bit patterns
     uint4 v[2];
+    template <bool NT>
     __device__ void load(const uint16_t *p) {
-        const uint4 *q = reinterpret_cast<const uint4 *>(p);
-        v[0] = q[0];
-        v[1] = q[1];
+        v[0] = load16<NT>(p);
+        v[1] = load16<NT>(p + 8);
     }
     __device__ void zero() { v[0] = v[1] = make_uint4(0, 0, 0, 0); }
     __device__ float get(int i) const {
@@ -163,7 +195,7 @@ constexpr int kMaxSlices = 8;
 // TENSOR: the absmax comes from `tmax` (one scale for the whole tensor).  A template parameter
 // rather than a test of tmax.partials, so that the per-token kernel is compiled exactly as if
 // the other did not exist.
-template <typename XT, bool TENSOR>
+template <typename XT, bool TENSOR, int POLICY>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
     uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax,
@@ -180,7 +212,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
-        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        if (live && ui < units) u[i].template load<POLICY == kStreamLoads>(xrow + (int64_t)ui * kUnit);
         else u[i].zero();
     }
 
@@ -222,10 +254,10 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_kernel(
             w[d] = codes4(quotient(u[i].get(4 * d + 0), s, r), quotient(u[i].get(4 * d + 1), s, r),
                           quotient(u[i].get(4 * d + 2), s, r), quotient(u[i].get(4 * d + 3), s, r), qmax);
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
-        if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
+        if (out_rows) store16<POLICY == kStreamStores>(out_rows + (int64_t)ui * kUnit, out);
         // unit ui covers k = 16 ui ..: 64-k stage ui / 4, k quarter ui % 4 (see act_frag_offset)
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
+            store16<POLICY == kStreamStores>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256, out);
     }
 }
 
@@ -252,7 +284,7 @@ __device__ inline float dpp_xor4(float v) {
     return __int_as_float(t);
 }
 
-template <typename XT>
+template <typename XT, int POLICY>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, int8_t *__restrict__ qx,
     uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale, float qmax, int rot) {
@@ -268,7 +300,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
-        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        if (live && ui < units) u[i].template load<POLICY == kStreamLoads>(xrow + (int64_t)ui * kUnit);
         else u[i].zero();
     }
 
@@ -331,9 +363,9 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
             w[d] = codes4(quotient(f[i][4 * d + 0], s, r), quotient(f[i][4 * d + 1], s, r),
                           quotient(f[i][4 * d + 2], s, r), quotient(f[i][4 * d + 3], s, r), qmax);
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
-        if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
+        if (out_rows) store16<POLICY == kStreamStores>(out_rows + (int64_t)ui * kUnit, out);
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
+            store16<POLICY == kStreamStores>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256, out);
     }
 }
 
@@ -343,7 +375,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_rot_kernel(
 // exact for these larger quotients as well, checked on the host).  `shifted` selects what is
 // stored: the canonical unsigned code and z, or, for the GEMM, code - shift as a signed byte
 // and the correction shift - z (shift = asym_code_shift(act_bits)).
-template <typename XT>
+template <typename XT, int POLICY>
 __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
     const XT *__restrict__ X, int64_t M, int64_t K, uint8_t *__restrict__ qx,
     uint8_t *__restrict__ qx_tiled, int64_t KF, float *__restrict__ x_scale,
@@ -360,7 +392,7 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
 #pragma unroll
     for (int i = 0; i < kUnitsPerThread; ++i) {
         const int ui = slice * kUnitsPerSlice + i * kLanesPerRow + sub;
-        if (live && ui < units) u[i].load(xrow + (int64_t)ui * kUnit);
+        if (live && ui < units) u[i].template load<POLICY == kStreamLoads>(xrow + (int64_t)ui * kUnit);
         else u[i].zero();
     }
 
@@ -422,9 +454,9 @@ __global__ __launch_bounds__(64 * kMaxSlices) void quant_rows_asym_kernel(
             w[d] = __builtin_amdgcn_perm(y[1], y[0], 0x0c0c0400u) | __builtin_amdgcn_perm(y[3], y[2], 0x04000c0cu);
         }
         const uint4 out = make_uint4(w[0], w[1], w[2], w[3]);
-        if (out_rows) *reinterpret_cast<uint4 *>(out_rows + (int64_t)ui * kUnit) = out;
+        if (out_rows) store16<POLICY == kStreamStores>(out_rows + (int64_t)ui * kUnit, out);
         if (out_tiled)
-            *reinterpret_cast<uint4 *>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256) = out;
+            store16<POLICY == kStreamStores>(out_tiled + (int64_t)(ui >> 2) * (4 * kFragBytes) + (ui & 3) * 256, out);
     }
 }
 
@@ -464,6 +496,30 @@ __global__ __launch_bounds__(kGenericThreads) void quant_rows_generic_kernel(
     }
 }
 
+// Measured with bf16 input at K = 1152 and 4608 (whole qc_qlinear, GEMM included): up to 226 MB
+// of input plus codes ordinary accesses are the fastest (non-temporal ones 8 % slower on the
+// quantization); from 339 MB on, while the codes alone stay below the cache size, non-temporal
+// loads leave the codes in the cache for the GEMM (M = 131072, K = 1152: quantization 83 -> 75 us,
+// whole call 545 -> 512 us); with more than 256 MiB of codes non-temporal stores win instead
+// (M = 131072, K = 4608: 324 -> 304 us, whole call 848 -> 836 us).
+int cache_policy(int64_t M, int64_t K, size_t x_elem_bytes) {
+    constexpr int64_t kLastLevelCache = (int64_t)256 << 20;
+    const int64_t codes = M * K, input = codes * (int64_t)x_elem_bytes;
+    if (codes > kLastLevelCache) return kStreamStores;
+    if (input + codes > kLastLevelCache) return kStreamLoads;
+    return kCachePlain;
+}
+
+// calls f(std::integral_constant<int, policy>) for the policy picked at run time
+template <typename F>
+hipError_t with_policy(int policy, F &&f) {
+    switch (policy) {
+        case kStreamLoads: return f(std::integral_constant<int, kStreamLoads>{});
+        case kStreamStores: return f(std::integral_constant<int, kStreamStores>{});
+        default: return f(std::integral_constant<int, kCachePlain>{});
+    }
+}
+
 template <typename XT>
 hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *qx_tiled,
                         int64_t KF, float *x_scale, float qmax, int rot, TensorMax tmax,
@@ -471,12 +527,16 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
     const int64_t units = K / kUnit;
     const int64_t slices = (units + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const bool vec = (K % kUnit == 0) && slices <= kMaxSlices;
+    const int policy = cache_policy(M, K, sizeof(XT));
     if (rot) {
         if (!vec || K % rot) return hipErrorInvalidValue;  // the entry points reject these first
         const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
-        quant_rows_rot_kernel<XT><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
-            X, M, K, qx, qx_tiled, KF, x_scale, qmax, rot);
-        return hipGetLastError();
+        return with_policy(policy, [&](auto pol) {
+            quant_rows_rot_kernel<XT, decltype(pol)::value>
+                <<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+                    X, M, K, qx, qx_tiled, KF, x_scale, qmax, rot);
+            return hipGetLastError();
+        });
     }
     if (!vec) {
         const int64_t blocks = (M + 3) / 4;
@@ -485,13 +545,18 @@ hipError_t launch_typed(const XT *X, int64_t M, int64_t K, int8_t *qx, uint8_t *
         return hipGetLastError();
     }
     const int64_t blocks = (M + kRowsPerBlock - 1) / kRowsPerBlock;
-    if (tmax.partials)
-        quant_rows_kernel<XT, true><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+    if (tmax.partials) {
+        // the tensor was read once already for its absmax: what the caches still hold of it helps
+        quant_rows_kernel<XT, true, kCachePlain><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
             X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
-    else
-        quant_rows_kernel<XT, false><<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
-            X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
-    return hipGetLastError();
+        return hipGetLastError();
+    }
+    return with_policy(policy, [&](auto pol) {
+        quant_rows_kernel<XT, false, decltype(pol)::value>
+            <<<dim3((unsigned)blocks), dim3((unsigned)(64 * slices)), 0, stream>>>(
+                X, M, K, qx, qx_tiled, KF, x_scale, qmax, tmax);
+        return hipGetLastError();
+    });
 }
 
 }  // namespace
@@ -508,12 +573,16 @@ hipError_t launch_quant_act_asym(const void *X, qc_dtype xdt, int64_t M, int64_t
     const int64_t slices = (K / kUnit + kUnitsPerSlice - 1) / kUnitsPerSlice;
     const dim3 grid((unsigned)((M + kRowsPerBlock - 1) / kRowsPerBlock)), block((unsigned)(64 * slices));
     if (xdt == QC_BF16)
-        quant_rows_asym_kernel<uint16_t><<<grid, block, 0, stream>>>(
-            (const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, x_aux, levels, shift, shifted);
-    else
-        quant_rows_asym_kernel<float><<<grid, block, 0, stream>>>(
+        return with_policy(cache_policy(M, K, 2), [&](auto pol) {
+            quant_rows_asym_kernel<uint16_t, decltype(pol)::value><<<grid, block, 0, stream>>>(
+                (const uint16_t *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, x_aux, levels, shift, shifted);
+            return hipGetLastError();
+        });
+    return with_policy(cache_policy(M, K, 4), [&](auto pol) {
+        quant_rows_asym_kernel<float, decltype(pol)::value><<<grid, block, 0, stream>>>(
             (const float *)X, M, K, qx_rowmajor, qx_tiled, KF, x_scale, x_aux, levels, shift, shifted);
-    return hipGetLastError();
+        return hipGetLastError();
+    });
 }
 
 bool quant_rotation_supported(int64_t K, int rot_block) {

@@ -939,16 +939,13 @@ def test_quant_act_tensor_bit_exact(act_bits, dtype, M, K):
     assert np.array_equal(qx.cpu().numpy(), q_ref)
 
 
-@pytest.mark.parametrize("how", ["token", "rot128", "asym", "tensor"])
-def test_quantizers_offsets_beyond_4_gib(how):
-    """2^19 + 5 rows of 4608 bf16 values: 4.8 GB of input and 2.4 GB of codes, past what 32-bit
-    byte offsets reach, on the kernel that cuts a row into four column slices.  X repeats a
-    generated block of 2048 rows, so the oracle's codes for the block are the expected codes of
-    every repetition (for the one-scale-per-tensor form too: the tensor's absmax is the block's)."""
-    period, M, K = 2048, (1 << 19) + 5, 4608
-    block = random_x(np.random.default_rng(23), period, K, "bf16")
+def _quantizer_on_a_repeated_block(how, dtype, M, K):
+    """X repeats a generated block of 2048 rows, so the oracle's codes for the block are the
+    expected codes of every repetition (for the one-scale-per-tensor form too: the tensor's
+    absmax is the block's); every code and scale of the large tensor is compared."""
+    period = 2048
+    block = random_x(np.random.default_rng(23), period, K, dtype)
     xd = dev(block).repeat((M + period - 1) // period, 1)[:M].contiguous()
-    assert xd.numel() * 2 > 1 << 32 and xd.numel() > 1 << 31
     aux = None
     if how == "token":
         q_ref, s_ref = oracle.quant_act(block)
@@ -983,6 +980,26 @@ def test_quantizers_offsets_beyond_4_gib(how):
         assert torch.equal(bits[reps * period:], z_ref_d[:rest])
     del qx, sx, codes
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("how", ["token", "rot128", "asym", "tensor"])
+def test_quantizers_offsets_beyond_4_gib(how):
+    """2^19 + 5 rows of 4608 bf16 values: 4.8 GB of input and 2.4 GB of codes, past what 32-bit
+    byte offsets reach, on the kernel that cuts a row into four column slices (and, with codes
+    beyond the last-level cache, the variant with non-temporal stores)."""
+    M, K = (1 << 19) + 5, 4608
+    assert M * K * 2 > 1 << 32 and M * K > 1 << 31
+    _quantizer_on_a_repeated_block(how, "bf16", M, K)
+
+
+@pytest.mark.parametrize("how", ["token", "rot128", "asym"])
+@pytest.mark.parametrize("dtype,M", [("bf16", 98304 + 5), ("f32", 65536 + 5)])
+def test_quantizers_sizes_that_stream_their_input(how, dtype, M):
+    """Input plus codes beyond 256 MiB with the codes below it: the kernel variant that reads X
+    with non-temporal loads."""
+    K = 1152
+    assert M * K <= 256 << 20 < M * K * ((2 if dtype == "bf16" else 4) + 1)
+    _quantizer_on_a_repeated_block(how, dtype, M, K)
 
 
 @pytest.mark.parametrize("bits,act_bits", [(8, 8), (4, 8), (4, 6)])
