@@ -116,7 +116,7 @@ __global__ __launch_bounds__(THREADS) void read_kernel(const float4 *__restrict_
 }
 
 // The same over two buffers at once (the access pattern of the latent-change reduction).
-template <int THREADS, int U>
+template <int THREADS, int U, int POLICY = 0>
 __global__ __launch_bounds__(THREADS) void read2_kernel(const float4 *__restrict__ a,
                                                         const float4 *__restrict__ b, float *out,
                                                         int64_t n4) {
@@ -127,8 +127,8 @@ __global__ __launch_bounds__(THREADS) void read2_kernel(const float4 *__restrict
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * THREADS + threadIdx.x;
-            v[u] = a[i < n4 ? i : 0];
-            w[u] = b[i < n4 ? i : 0];
+            v[u] = ld16<POLICY>(a + (i < n4 ? i : 0));
+            w[u] = ld16<POLICY>(b + (i < n4 ? i : 0));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) s += v[u].x + w[u].w;
@@ -368,25 +368,31 @@ int main(int argc, char **argv) {
         CK(hipEventCreate(&e0));
         CK(hipEventCreate(&e1));
         for (int cold = 1; cold >= 0; --cold) {
-            float sum = 0;
-            const int rounds = 10, batch = 24;
-            for (int r = -300; r < rounds; ++r) {   // about 50 ms of the same launches first
-                CK(hipEventRecord(e0));
-                for (int i = 0; i < batch; ++i) {
-                    const int64_t off = cold ? (int64_t)(i % 12) * 2 * m : 0;
-                    read2_kernel<1024, 4><<<CU, 1024>>>((const float4 *)((const char *)a + off),
-                                                        (const float4 *)((const char *)a + off + m),
-                                                        (float *)dout, m / 16);
+            double us_of[2];
+            for (int nt = 0; nt < 2; ++nt) {   // ordinary loads, then non-temporal ones
+                float sum = 0;
+                const int rounds = 10, batch = 24;
+                for (int r = -300; r < rounds; ++r) {   // about 50 ms of the same launches first
+                    CK(hipEventRecord(e0));
+                    for (int i = 0; i < batch; ++i) {
+                        const int64_t off = cold ? (int64_t)(i % 12) * 2 * m : 0;
+                        const float4 *p = (const float4 *)((const char *)a + off), *q = (const float4 *)((const char *)a + off + m);
+                        if (nt) read2_kernel<1024, 4, 1><<<CU, 1024>>>(p, q, (float *)dout, m / 16);
+                        else read2_kernel<1024, 4, 0><<<CU, 1024>>>(p, q, (float *)dout, m / 16);
+                    }
+                    CK(hipEventRecord(e1));
+                    CK(hipEventSynchronize(e1));
+                    float t;
+                    CK(hipEventElapsedTime(&t, e0, e1));
+                    if (r >= 0) sum += t / batch;
                 }
-                CK(hipEventRecord(e1));
-                CK(hipEventSynchronize(e1));
-                float t;
-                CK(hipEventElapsedTime(&t, e0, e1));
-                if (r >= 0) sum += t / batch;
+                us_of[nt] = sum / rounds * 1e3;
             }
-            const double us = sum / rounds * 1e3;
-            printf("hbm  read-only, 2 x 16 MiB per launch, %s: %6.2f us per launch, %7.0f GB/s\n",
-                   cold ? "cold (12 pairs in turn)" : "warm (one pair, cache resident)", us, 2.0 * m / us * 1e-3);
+            const double us = us_of[0] < us_of[1] ? us_of[0] : us_of[1];
+            printf("hbm  read-only, 2 x 16 MiB per launch, %s (ordinary / non-temporal loads: %.2f / %.2f): "
+                   "%6.2f us per launch, %7.0f GB/s\n",
+                   cold ? "cold (12 pairs in turn)" : "warm (one pair again and again)", us_of[0], us_of[1], us,
+                   2.0 * m / us * 1e-3);
             printf("@read_32mib_%s_us %.2f\n", cold ? "cold" : "warm", us);
         }
         CK(hipFree(a));
