@@ -266,6 +266,22 @@ qc_status qc_qlinear_tensor(const void *X, qc_dtype xdt, int64_t M, int64_t K, i
 qc_status qc_debug_workspace_act(const void *workspace, int64_t M, int64_t K, int8_t *qx,
                                  float *x_scale, void *stream);
 
+/* Test hooks for the GEMM stage, host only (no device is touched).  The GEMM (Section 4.1
+ * "Hardware Implementation") exists as two kernels: one streams the weight tile of a block through
+ * a ring in LDS, the other keeps a whole 128-channel weight tile resident in LDS and is taken for
+ * short reductions (K <= 1152 with 8-bit weights, <= 2304 with 4-bit ones) on problems large
+ * enough for its static schedule.
+ *   qc_debug_gemm_kernel    which one qc_qlinear_gemm takes for (M, K, N, bits): 1 the ring,
+ *                           2 the resident one, 0 if the shape is unsupported
+ *   qc_debug_gemm_schedule  the rounds of block `block` (0 .. 255) of the resident kernel for an
+ *                           [M, N] output, in the order the block runs them: pairs[2 i] is the
+ *                           128-channel tile, pairs[2 i + 1] the 512-token chunk of round i.
+ *                           Returns the number of rounds and fills at most `cap` pairs (host
+ *                           memory; may be NULL with cap 0); -1 for bad arguments.  Over all
+ *                           blocks every (tile, chunk) appears exactly once. */
+int qc_debug_gemm_kernel(int64_t M, int64_t K, int64_t N, int bits);
+int qc_debug_gemm_schedule(int64_t M, int64_t N, int block, int32_t *pairs, int cap);
+
 /* ---- S5: latent change reduction ----------------------------------------------------
  * Section 3.2 HLC, Eq. (5): the L1 norm of the change between the current latent and
  * the cached one, with the L1 norm of the cached one to make it relative.

@@ -26,7 +26,8 @@ EXPORTS = (
     "qc_latent_delta_workspace_bytes", "qc_pack_weight", "qc_unpack_weight_codes", "qc_quant_act",
     "qc_qlinear", "qc_qlinear_quant", "qc_qlinear_gemm", "qc_quant_act_bits",
     "qc_qlinear_quant_bits", "qc_qlinear_act_bits", "qc_layer_similarity_workspace_bytes",
-    "qc_layer_similarity", "qc_debug_workspace_act", "qc_latent_delta",
+    "qc_layer_similarity", "qc_debug_workspace_act", "qc_debug_gemm_kernel", "qc_debug_gemm_schedule",
+    "qc_latent_delta",
     "qc_frame_gradient_norm_workspace_bytes", "qc_frame_gradient_norm",
     "qc_cumulative_variation_workspace_bytes", "qc_cumulative_variation",
     "qc_divergence_score", "qc_cache_interval", "qc_activation_bits", "qc_prune_probability",
@@ -90,6 +91,10 @@ def lib() -> ctypes.CDLL:
         L.qc_layer_similarity.argtypes = [vp, vp, i32, i64, vp, vp, sz, vp]
         L.qc_debug_workspace_act.restype = i32
         L.qc_debug_workspace_act.argtypes = [vp, i64, i64, vp, vp, vp]
+        L.qc_debug_gemm_kernel.restype = i32
+        L.qc_debug_gemm_kernel.argtypes = [i64, i64, i64, i32]
+        L.qc_debug_gemm_schedule.restype = i32
+        L.qc_debug_gemm_schedule.argtypes = [i64, i64, i32, vp, i32]
         L.qc_latent_delta.restype = i32
         L.qc_latent_delta.argtypes = [vp, vp, i64, vp, vp, sz, vp]
         L.qc_latent_delta_static.restype = i32
@@ -223,6 +228,24 @@ def qc_layer_similarity(a, b, dt, n, out4, workspace, workspace_bytes, stream=0)
 
 def qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream=0) -> int:
     return int(lib().qc_debug_workspace_act(workspace, M, K, qx, x_scale, stream))
+
+
+def qc_debug_gemm_kernel(M, K, N, bits) -> int:
+    return int(lib().qc_debug_gemm_kernel(M, K, N, bits))
+
+
+def qc_debug_gemm_schedule(M, N, block, pairs, cap) -> int:
+    return int(lib().qc_debug_gemm_schedule(M, N, block, pairs, cap))
+
+
+def gemm_schedule(M: int, N: int, block: int):
+    """The (channel tile, token chunk) rounds of one block of the resident GEMM kernel (host only)."""
+    n = qc_debug_gemm_schedule(M, N, block, None, 0)
+    if n < 0:
+        raise QcError(QC_ERR_INVALID_ARG, "qc_debug_gemm_schedule")
+    buf = (ctypes.c_int32 * (2 * max(n, 1)))()
+    qc_debug_gemm_schedule(M, N, block, ctypes.cast(buf, ctypes.c_void_p), n)
+    return [(buf[2 * i], buf[2 * i + 1]) for i in range(n)]
 
 
 def qc_latent_delta(cur, prev, n, out3, workspace, workspace_bytes, stream=0) -> int:

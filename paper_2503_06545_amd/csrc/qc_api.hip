@@ -217,7 +217,7 @@ extern "C" qc_status qc_qlinear_gemm(const void *workspace, size_t workspace_byt
     const uint8_t *base = (const uint8_t *)workspace;
     return device_status(launch_gemm(base + ws.scale_bytes, (const float *)base,
                                      (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
-                                     ydt, nullptr, nullptr, (hipStream_t)stream));
+                                     ydt, nullptr, nullptr, kGemmAuto, (hipStream_t)stream));
 }
 
 extern "C" qc_status qc_qlinear_act_bits(const void *X, qc_dtype xdt, int64_t M, int64_t K,
@@ -296,7 +296,7 @@ extern "C" qc_status qc_qlinear_asym_gemm(const void *workspace, size_t workspac
     return device_status(launch_gemm(base + ws.codes_offset, (const float *)base,
                                      (const uint8_t *)packed, w_scale, bias, Y, M, N, K, bits, epi,
                                      ydt, (const float *)(base + ws.corr_offset), w_row_sums,
-                                     (hipStream_t)stream));
+                                     kGemmAuto, (hipStream_t)stream));
 }
 
 extern "C" qc_status qc_qlinear_asym(const void *X, qc_dtype xdt, int64_t M, int64_t K,
@@ -361,4 +361,18 @@ extern "C" qc_status qc_qlinear_tensor(const void *X, qc_dtype xdt, int64_t M, i
                                                  (hipStream_t)stream)));
     return qc_qlinear_gemm(workspace, workspace_bytes, M, K, packed, w_scale, bits, N, bias, epi, Y,
                            ydt, stream);
+}
+
+// ---- test hooks for the GEMM's choice of kernel and its static schedule (host only) -------------
+
+extern "C" int qc_debug_gemm_kernel(int64_t M, int64_t K, int64_t N, int bits) {
+    if (M < 1 || K < 1 || N < 1 || check_gemm_supported(M, K, N, bits) != QC_OK) return 0;
+    return gemm_resident_chosen(M, N, K, bits) ? 2 : 1;
+}
+
+extern "C" int qc_debug_gemm_schedule(int64_t M, int64_t N, int block, int32_t *pairs, int cap) {
+    if (M < 1 || N < 1 || block < 0 || block >= gemm_resident_blocks() || cap < 0) return -1;
+    const int64_t m_tiles = round_up(M, kTileM) / kTileM, n_tiles = round_up(N, kTileN) / kTileN;
+    if (m_tiles * n_tiles > 0x7fffffffLL) return -1;
+    return resident_block_rounds(block, gemm_resident_blocks(), (int)n_tiles, (int)m_tiles, pairs, cap);
 }

@@ -139,9 +139,108 @@ __host__ inline ActWorkspaceAsym act_workspace_asym(int64_t M, int64_t K) {
     return w;
 }
 
+// ---- schedule of the GEMM kernel that keeps its weight tile in LDS ---------------------------
+constexpr int kRoundTokens = 512;   // one round: a channel tile x 512 tokens, 64 per wavefront
+
+// rounds of 512 tokens over the padded token count (m_tiles tiles of 256)
+__host__ __device__ inline int resident_chunks(int m_tiles) { return m_tiles / 2 + (m_tiles & 1); }
+
+// Block b of a launch of nb blocks runs on XCD b % 8; the XCDs split the token chunks evenly.
+struct ResidentXcd {
+    int slot, blocks;   // the block's index among the blocks of its XCD, and how many those are
+    int c_lo, c_hi;     // the XCD's chunks
+};
+
+__host__ __device__ inline ResidentXcd resident_xcd(int b, int nb, int chunks) {
+    ResidentXcd x;
+    const int xcd = b % 8;
+    x.slot = b / 8;
+    x.blocks = nb / 8 + (xcd < nb % 8 ? 1 : 0);
+    x.c_lo = (int)((int64_t)chunks * xcd / 8);
+    x.c_hi = (int)((int64_t)chunks * (xcd + 1) / 8);
+    return x;
+}
+
+// The static schedule of the resident kernel on one XCD: `blocks` blocks (one per CU) share
+// `chunks` rounds of 512 tokens x `n_tiles` channel tiles.  Two things decide it: a block should
+// keep its weight tile for many rounds, and the blocks of the XCD should be reading the same few
+// token chunks at the same time, because the XCD's L2 (4 MB) can hold the activations of a handful
+// of chunks (576 KiB each at K = 1152) and the fabric behind it cannot deliver them once per
+// channel tile (measured: with every block on its own chunk the kernel runs at the fabric's
+// 5.7 TB/s, 55 % slower).  Channel tiles are taken in passes of at most `blocks`; within a pass of
+// t tiles, k = blocks / t groups of t blocks each walk their own run of chunks in step, one
+// channel tile per block, and the blocks left over share the remaining chunks x all t tiles in
+// tile-major order.  A block's rounds of a pass are ids [id0, id1) with channel tile
+// nt_off + id / w and chunk c_off + id % w.
+struct RoundRange {
+    int id0, id1, w, nt_off, c_off;
+};
+
+__host__ __device__ inline RoundRange resident_rounds(int pass, int slot, int blocks, int n_tiles, int chunks) {
+    const int t = n_tiles - pass * blocks < blocks ? n_tiles - pass * blocks : blocks;
+    const int k = blocks / t, main_n = k * t, side_n = blocks - main_n;
+    int cm = 0, side0 = chunks;   // chunks per group, first chunk of the left-over blocks
+    if (side_n > 0) {
+        // the nearest split to equal rounds for everybody
+        const int lo = (int)((int64_t)t * chunks / blocks);
+        int best = -1;
+        for (int c = lo; c <= lo + 1; ++c) {
+            if ((int64_t)k * c > chunks) continue;
+            const int side_r = (int)(((int64_t)t * (chunks - k * c) + side_n - 1) / side_n);
+            const int cost = c > side_r ? c : side_r;
+            if (best < 0 || cost < best) { best = cost; cm = c; }
+        }
+        side0 = k * cm;
+    }
+    RoundRange r;
+    if (slot < main_n) {
+        const int j = slot / t;
+        const int g_lo = side_n ? j * cm : (int)((int64_t)chunks * j / k);
+        const int g_hi = side_n ? (j + 1) * cm : (int)((int64_t)chunks * (j + 1) / k);
+        r.id0 = 0;
+        r.id1 = g_hi - g_lo;
+        r.w = r.id1 > 0 ? r.id1 : 1;
+        r.nt_off = pass * blocks + slot % t;
+        r.c_off = g_lo;
+    } else {
+        const int q = slot - main_n, cs = chunks - side0;
+        const int64_t total = (int64_t)t * cs;
+        r.id0 = (int)(total * q / side_n);
+        r.id1 = (int)(total * (q + 1) / side_n);
+        r.w = cs > 0 ? cs : 1;
+        r.nt_off = pass * blocks;
+        r.c_off = side0;
+    }
+    return r;
+}
+
+
+// The rounds of block b in the order it runs them, as (channel tile, chunk) pairs; returns their
+// number and writes the first `cap` of them to `pairs` (2 ints each) when it is not null.
+__host__ __device__ inline int resident_block_rounds(int b, int nb, int n_tiles, int m_tiles, int *pairs, int cap) {
+    const ResidentXcd x = resident_xcd(b, nb, resident_chunks(m_tiles));
+    int n = 0;
+    for (int pass = 0; pass * x.blocks < n_tiles; ++pass) {
+        const RoundRange r = resident_rounds(pass, x.slot, x.blocks, n_tiles, x.c_hi - x.c_lo);
+        for (int id = r.id0; id < r.id1; ++id, ++n)
+            if (pairs && n < cap) {
+                pairs[2 * n] = r.nt_off + id / r.w;
+                pairs[2 * n + 1] = x.c_lo + r.c_off + id % r.w;
+            }
+    }
+    return n;
+}
+
+enum GemmKernel { kGemmAuto = 0, kGemmRing = 1, kGemmResident = 2 };
+// whether a 128-channel weight tile of this reduction length fits the resident kernel's LDS
+bool gemm_resident_fits(int64_t K, int bits);
+// whether launch_gemm picks the resident kernel for this problem by itself
+bool gemm_resident_chosen(int64_t M, int64_t N, int64_t K, int bits);
+int gemm_resident_blocks();
+
 hipError_t launch_gemm(const uint8_t *x_tiled, const float *x_scale, const uint8_t *w_packed,
                        const float *w_scale, const float *bias, void *Y, int64_t M, int64_t N,
                        int64_t K, int bits, qc_epilogue epi, qc_out ydt, const float *x_corr,
-                       const int32_t *w_rowsum, hipStream_t stream);
+                       const int32_t *w_rowsum, GemmKernel which, hipStream_t stream);
 
 }  // namespace qc

@@ -540,6 +540,51 @@ def test_config_sweep28_sampled_rows(kind, bits):
         _sweep_x.clear()
 
 
+@pytest.mark.parametrize("bits,K,epi,out,asym", [
+    (8, 1000, "gelu_tanh", "bf16", False), (8, 1152, "none", "f32", False),
+    (4, 2200, "gelu_erf", "bf16", False), (4, 1136, "none", "f32", True),
+    (8, 1136, "gelu_tanh", "bf16", True)])
+def test_qlinear_weights_resident_in_lds_ragged_shapes(bits, K, epi, out, asym):
+    """The GEMM kernel that keeps its weight tile in LDS, on a problem it is chosen for whose
+    edges are all ragged: 80037 tokens (the last 512-token round and the last 64-token tile are
+    partial), 3401 channels (a partial last channel tile, scalar stores), K below the padded
+    reduction length.  X repeats a block of 1024 generated rows, so the oracle's result for the
+    block is the expected result of every repetition: all outputs are compared."""
+    period, M, N = 1024, 80037, 3401
+    assert qc.qc_debug_gemm_kernel(M, K, N, bits) == 2
+    rng = np.random.default_rng(1000 * bits + K)
+    block = post_gelu_x(rng, period, K, "bf16") if asym else random_x(rng, period, K, "bf16")
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+    qw_ref, sw_ref = oracle.quant_weight(W, bits)
+    xd = dev(block).repeat((M + period - 1) // period, 1)[:M].contiguous()
+    pw = qc.pack_weight_t(dev(W), bits)
+    if asym:
+        ref = oracle.qlinear_asym(block, qw_ref, sw_ref, b, EPI_ORACLE[epi], 8)
+        rs = qc.weight_row_sums_t(pw)
+        ws = qc.qlinear_asym_workspace_t(M, K, N)
+        y = qc.qlinear_asym_t(xd, pw, rs, dev(b), epi, out, workspace=ws)
+        acc = qc.qlinear_asym_t(xd, pw, rs, None, "none", "i32", workspace=ws)
+        acc_ref = oracle.gemm_i32((ref["qx"].astype(np.int16) - 128).astype(np.int8), qw_ref)
+    else:
+        ref = oracle.qlinear(block, qw_ref, sw_ref, b, EPI_ORACLE[epi])
+        ws = qc.qlinear_workspace_t(M, K, N)
+        y = qc.qlinear_t(xd, pw, dev(b), epi, out, workspace=ws)
+        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+        acc_ref = ref["acc"]
+    torch.cuda.synchronize()
+    assert y.shape == (M, N) and acc.shape == (M, N)
+    assert np.array_equal(acc[:period].cpu().numpy(), acc_ref)
+    y_ref = ref["y"]
+    y_ref = (oracle.bf16_bits_to_f64(oracle.round_bf16_bits(y_ref)) if out == "bf16"
+             else oracle.round_f32(y_ref).astype(np.float64))
+    assert_outputs_close(host_f64(y[:period]), y_ref, RTOL[out])
+    # every other row against the one a period above it, bit for bit
+    assert torch.equal(acc[period:], acc[:-period])
+    as_int = torch.int16 if out == "bf16" else torch.int32
+    assert torch.equal(y[period:].view(as_int), y[:-period].view(as_int))
+
+
 def test_qlinear_offsets_beyond_4_gib():
     """A problem whose input passes 2 GiB and whose output passes 4 GiB, so that a 32-bit byte or
     element offset anywhere on the path would wrap: M = 2^19 + 77 tokens of 1152 binary32 values
