@@ -745,10 +745,16 @@ bool gemm_resident_chosen(int64_t M, int64_t N, int64_t K, int bits) {
     const int m_tiles = (int)(round_up(M, kTileM) / kTileM), n_tiles = (int)(round_up(N, kTileN) / kTileN);
     const int64_t total = (int64_t)n_tiles * resident_chunks(m_tiles);
     if (total < 16 * kResBlocks) return false;
-    int most = 0;
-    for (int b = 0; b < kResBlocks; ++b) {
-        const int r = resident_block_rounds(b, kResBlocks, n_tiles, m_tiles, nullptr, 0);
-        most = r > most ? r : most;
+    int most = 0, seen[2] = {-1, -1};   // the XCDs' chunk counts differ by one at most
+    for (int xcd = 0; xcd < 8; ++xcd) {
+        const ResidentXcd x = resident_xcd(xcd, kResBlocks, resident_chunks(m_tiles));
+        const int cx = x.c_hi - x.c_lo;
+        if (cx == seen[0] || cx == seen[1]) continue;
+        seen[seen[0] < 0 ? 0 : 1] = cx;
+        for (int slot = 0; slot < x.blocks; ++slot) {
+            const int r = resident_block_rounds(xcd + 8 * slot, kResBlocks, n_tiles, m_tiles, nullptr, 0);
+            most = r > most ? r : most;
+        }
     }
     return (int64_t)most * kResBlocks * 100 <= total * 104;
 }
