@@ -585,6 +585,43 @@ def test_qlinear_weights_resident_in_lds_ragged_shapes(bits, K, epi, out, asym):
     assert torch.equal(y[period:].view(as_int), y[:-period].view(as_int))
 
 
+def test_qlinear_weights_resident_in_lds_seeded_shapes():
+    """Seeded shapes the resident-weight kernel is chosen for, from the shortest reduction (three
+    64-k stages) to the longest that fits, with channel counts on both sides of a pass of 32
+    channel tiles; raw accumulators and bf16 outputs of every row against the oracle's result for
+    the repeated block of rows."""
+    rng = np.random.default_rng(77)
+    period, done = 512, 0
+    for bits, K in ((8, 192), (8, 330), (4, 2304), (8, 768), (4, 96), (8, 1152)):
+        for _ in range(40):
+            M = int(rng.integers(66000, 150000))
+            N = int(rng.integers(2100, 6000))
+            if qc.qc_debug_gemm_kernel(M, K, N, bits) == 2:
+                break
+        else:
+            raise AssertionError("no shape found that takes the resident kernel")
+        block = random_x(rng, period, K, "bf16")
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float32)
+        qw_ref, sw_ref = oracle.quant_weight(W, bits)
+        ref = oracle.qlinear(block, qw_ref, sw_ref, b, oracle.EPI_NONE)
+        xd = dev(block).repeat((M + period - 1) // period, 1)[:M].contiguous()
+        pw = qc.pack_weight_t(dev(W), bits)
+        ws = qc.qlinear_workspace_t(M, K, N)
+        y = qc.qlinear_t(xd, pw, dev(b), "none", "bf16", workspace=ws)
+        acc = qc.qlinear_t(xd, pw, None, "none", "i32", workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc[:period].cpu().numpy(), ref["acc"]), (M, K, N, bits)
+        assert torch.equal(acc[period:], acc[:-period]), (M, K, N, bits)
+        y_ref = oracle.bf16_bits_to_f64(oracle.round_bf16_bits(ref["y"]))
+        assert_outputs_close(host_f64(y[:period]), y_ref, RTOL["bf16"])
+        assert torch.equal(y[period:].view(torch.int16), y[:-period].view(torch.int16)), (M, K, N, bits)
+        del xd, y, acc, ws
+        done += 1
+    assert done == 6
+    torch.cuda.empty_cache()
+
+
 def test_qlinear_offsets_beyond_4_gib():
     """A problem whose input passes 2 GiB and whose output passes 4 GiB, so that a 32-bit byte or
     element offset anywhere on the path would wrap: M = 2^19 + 77 tokens of 1152 binary32 values
