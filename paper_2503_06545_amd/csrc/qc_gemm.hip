@@ -735,16 +735,17 @@ bool gemm_resident_fits(int64_t K, int bits) {
     return KF * (bits == 8 ? StageLayout<8>::kBytes : StageLayout<4>::kBytes) <= kResWeightBytes;
 }
 
-// The resident kernel is taken when the weight tile fits, every block gets at least 16 rounds
-// (below that the weight tile it loads first and the last, partly idle rounds weigh too much: the
-// out-projection 1152 -> 1152 at M = 131072, 9 rounds, is 3 % slower on it) and the static
-// schedule is within 4 % of an even split.  Measured at M = 131072: QKV 434 -> 420 us,
-// fc1 + GELU 650 -> 625 us; at M = 65536 fc1 + GELU 326 -> 316 us.
+// The resident kernel is taken when the weight tile fits, the blocks get 6 rounds or more on
+// average and the static schedule is within 4 % of an even split.  Measured against the ring
+// kernel at K = 1152 (rounds per block: gain): 3.4: -9 %, 4.5: -6 % (the weight tile a block loads
+// first and its last, partly idle rounds weigh too much), 6.8: +3.5 %, 9: 0 to +2.5 %, 13.5: +4 %,
+// 18: +2 to +9 %, 27 (QKV at M = 131072): 434 -> 420 us, 36 (fc1 + GELU): 650 -> 625 us; K = 384,
+// 36 rounds: +10 %.
 bool gemm_resident_chosen(int64_t M, int64_t N, int64_t K, int bits) {
     if (!gemm_resident_fits(K, bits)) return false;
     const int m_tiles = (int)(round_up(M, kTileM) / kTileM), n_tiles = (int)(round_up(N, kTileN) / kTileN);
     const int64_t total = (int64_t)n_tiles * resident_chunks(m_tiles);
-    if (total < 16 * kResBlocks) return false;
+    if (total < 6 * kResBlocks) return false;
     int most = 0, seen[2] = {-1, -1};   // the XCDs' chunk counts differ by one at most
     for (int xcd = 0; xcd < 8; ++xcd) {
         const ResidentXcd x = resident_xcd(xcd, kResBlocks, resident_chunks(m_tiles));
