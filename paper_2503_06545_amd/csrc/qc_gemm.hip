@@ -4,7 +4,11 @@
 //   acc[m, n] = sum_k qx[m, k] * qw[n, k]          exact, int32, v_mfma_i32_16x16x64_i8
 //   Y[m, n]   = act(acc * sx[m] * sw[n] + bias[n])
 //
-// Block tile 256 tokens x 128 channels, 4 wavefronts stacked along the tokens, each
+// Two kernels share the wavefront tile, the operand formats and the epilogue: gemm_kernel
+// streams its weight tile through a ring in LDS and takes any K; gemm_resident_kernel (further
+// down) keeps a whole weight tile in LDS and is taken for short reductions on large problems.
+//
+// gemm_kernel: block tile 256 tokens x 128 channels, 4 wavefronts stacked along the tokens, each
 // 64 x 128 = 4 x 8 MFMA tiles (128 accumulator registers), two blocks per CU so that one
 // block's epilogue overlaps the other's MFMA loop.  Operands arrive pre-arranged as 1 KiB
 // MFMA fragments (see qc_internal.h).  The weight tile, which all four wavefronts use, goes
@@ -473,9 +477,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 // block of eight wavefronts, one per CU, loads it once and then every wavefront walks token tiles
 // of 64 on its own: no weight copies and no block barriers inside the reduction, which is what
 // the ring version above spends 5-9 % of its time on when K is 1152.  Work is cut into rounds of
-// (channel tile, 512 tokens = one 64-token tile per wavefront); the rounds of one XCD (its eighth
-// of the tokens x all channel tiles) are dealt to its blocks as contiguous runs in channel-tile-major order,
-// so a block changes its weight tile once or twice per launch.
+// (channel tile, 512 tokens = one 64-token tile per wavefront) and dealt to the blocks by the
+// static schedule of resident_rounds() (qc_internal.h): a block changes its weight tile once or
+// twice per launch, and the blocks of an XCD read the same few token chunks at the same time.
 constexpr int kResThreads = 512;
 constexpr int kResWaves = kResThreads / 64;
 static_assert(kRoundTokens == kResWaves * kWaveM, "a round is one 64-token tile per wavefront");
