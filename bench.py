@@ -377,6 +377,11 @@ class Bench:
             self.x_dev[key] = self.torch.from_numpy(bits.view(np.int16)).cuda().view(self.torch.bfloat16)
         return self.x_dev[key][:case.M]
 
+    def gemm_kernel_name(self, case):
+        """Which of the GEMM's two kernels the library takes for this layer."""
+        which = self.qc.qc_debug_gemm_kernel(case.M, case.K, case.N, case.bits)
+        return "gemm_resident_kernel" if which == 2 else "gemm_kernel"
+
     def check(self, st):
         if st != self.qc.QC_OK:
             raise self.qc.QcError(st, "bench step")
@@ -513,7 +518,7 @@ class Bench:
             "ms_per_step": round(ms_per_step, 5), "value": round(value, 2), "unit": "TOPS",
             "frac_of_peak": round(value / PEAK_INT8_TOPS, 4),
             "device": device,
-            "roofline": self.mfma_roofline(name, f"gemm_kernel<{case.bits}, bf16, {case.epi}>", L.ops,
+            "roofline": self.mfma_roofline(name, f"{self.gemm_kernel_name(case)}<{case.bits}, bf16, {case.epi}>", L.ops,
                                            gemm["avg_us"], 1),
             "kernels": {
                 "quant_act": self.hbm_entry(quant_bytes, quant["avg_us"], traffic=tr.get("quant")),
@@ -622,6 +627,7 @@ class Bench:
             tops = sum(L.ops for L in ls) / (t["avg_us"] * 1e-6) / 1e12
             qbytes = (c.M * c.K * 3 + 4 * c.M)
             classes.append({"layer": kind, "K": c.K, "N": c.N, "weight_bits": bits, "layers": len(ls),
+                            "gemm_kernel": self.gemm_kernel_name(c),
                             "gemm_avg_launch_us": round(t["avg_us"] / len(ls), 1),
                             "gemm_tops": round(tops, 1), "gemm_frac": round(tops / PEAK_INT8_TOPS, 4),
                             "quant_avg_launch_us": round(q["avg_us"] / len(ls), 1),
@@ -636,7 +642,7 @@ class Bench:
             "steps": steps, "warmup": warmup, "preload_s": PRELOAD_SECONDS,
             "ms_per_step": round(ms_per_step, 4), "value": round(value, 2), "unit": "TOPS",
             "frac_of_peak": round(value / PEAK_INT8_TOPS, 4), "device": device,
-            "roofline": self.mfma_roofline("sweep28", "gemm_kernel<8|4, bf16, none|gelu_tanh> (112 launches)",
+            "roofline": self.mfma_roofline("sweep28", "gemm_resident_kernel | gemm_kernel<8|4, bf16, none|gelu_tanh> (112 launches)",
                                            ops, gemm["avg_us"], n),
             "kernels": {
                 "quant_act": self.hbm_entry(quant_bytes / n, quant["avg_us"] / n, traffic=tr.get("quant")),
